@@ -1,0 +1,134 @@
+"""CPU oracle for the EpiCache eviction step.  TEST INFRASTRUCTURE ONLY.
+
+This is the plain definition of what one eviction step of block-wise prefill
+computes, written from the paper and evaluated in float64 with numpy.  It is
+slow on purpose, shares no code with the HIP path and must never be imported by
+the product package: only tests/, __graft_entry__.smoke() and bench.py's
+cpu_baseline leg may use it.
+
+What the paper fixes and what is a reading of it:
+  * importance of context token i = attention weight it receives from the
+    patched-prompt queries, reduced over the query tokens with max (Sec. 2.3,
+    Eq. 1).  REDUCE_SUM (sum of the weights, "attention mass") is the variant
+    the benchmark spec asks for next to it.
+  * the top M tokens are kept (Sec. 3.1 Stage 2; Alg. 1 phase A3), so that the
+    cache returns to size M after growing to M + M_block (Sec. 2.2, App. A.3).
+  * readings where the paper is silent: the G query heads of a GQA group vote
+    for their KV head with the same operator as the query tokens; the softmax
+    is over the N context keys only; logits are scaled by 1/sqrt(d); ties go to
+    the lower index; kept rows stay in their original order.
+Which reduction and softmax denominator the authors' own runs used cannot be
+checked against anything (no code, no numbers in the paper): parity unpinned
+for that choice; both reductions are implemented.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+REDUCE_MAX = 0  # Eq. 1
+REDUCE_SUM = 1
+
+
+def attention_weights(q_rows: np.ndarray, k_ctx: np.ndarray, scale: float) -> np.ndarray:
+    """Attn(x_t -> x_i) for every query row t and context key i (Sec. 2.3).
+
+    q_rows [R, d], k_ctx [N, d] float64.  Row-wise softmax of scale * q.k over
+    the N context keys.  Returns [R, N].
+    """
+    z = scale * (q_rows @ k_ctx.T)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def score(q: np.ndarray, k: np.ndarray, n_ctx: int, reduce: int = REDUCE_MAX,
+          scale: float | None = None) -> np.ndarray:
+    """Importance s[b, h, i] of context token i for KV head h of batch item b.
+
+    q [nb, Hq, p, d], k [nb, Hkv, C >= n_ctx, d] (any float dtype, widened to
+    float64).  Query head hq votes for KV head hq // G, G = Hq / Hkv.
+    Eq. 1 with the reduction taken over the G * p rows of the group.
+    Returns float64 [nb, Hkv, n_ctx].
+    """
+    nb, Hq, p, d = q.shape
+    Hkv = k.shape[1]
+    assert Hq % Hkv == 0 and k.shape[0] == nb and k.shape[3] == d and k.shape[2] >= n_ctx
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((nb, Hkv, n_ctx), dtype=np.float64)
+    for b in range(nb):
+        for h in range(Hkv):
+            rows = np.asarray(q[b, h * G:(h + 1) * G], dtype=np.float64).reshape(G * p, d)
+            keys = np.asarray(k[b, h, :n_ctx], dtype=np.float64)
+            attn = attention_weights(rows, keys, scale)
+            out[b, h] = attn.max(axis=0) if reduce == REDUCE_MAX else attn.sum(axis=0)
+    return out
+
+
+def topk_1d(s: np.ndarray, M: int) -> np.ndarray:
+    """Indices of the min(M, N) largest entries of s, ascending; ties -> lower index."""
+    N = s.shape[0]
+    keep = min(M, N)
+    order = np.lexsort((np.arange(N), -s))  # primary: score descending, secondary: index
+    return np.sort(order[:keep]).astype(np.int32)
+
+
+def topk(scores: np.ndarray, M: int) -> np.ndarray:
+    """Per (b, h) top-M retention (Sec. 3.1 Stage 2).  scores [nb, Hkv, N] -> int32 [nb, Hkv, min(M,N)]."""
+    nb, Hkv, N = scores.shape
+    out = np.empty((nb, Hkv, min(M, N)), dtype=np.int32)
+    for b in range(nb):
+        for h in range(Hkv):
+            out[b, h] = topk_1d(scores[b, h], M)
+    return out
+
+
+def topk_by_counting(s, M: int):
+    """The same set from the counting definition, O(N^2), pure Python, tiny inputs only.
+
+    Token i is kept iff fewer than M tokens beat it, where j beats i when
+    s_j > s_i, or s_j == s_i and j < i.
+    """
+    N = len(s)
+    kept = []
+    for i in range(N):
+        beaten_by = 0
+        for j in range(N):
+            if s[j] > s[i] or (s[j] == s[i] and j < i):
+                beaten_by += 1
+        if beaten_by < M:
+            kept.append(i)
+    return kept
+
+
+def compact(x: np.ndarray, keep_idx: np.ndarray) -> np.ndarray:
+    """Rows keep_idx[b, h, :] of x[b, h] moved to the front, in order (Sec. 2.2, App. A.3).
+
+    x [nb, Hkv, C, d] of any dtype (bit patterns are copied, no arithmetic).
+    Returns a new array [nb, Hkv, n_keep, d].
+    """
+    nb, Hkv = keep_idx.shape[:2]
+    out = np.empty((nb, Hkv, keep_idx.shape[2], x.shape[3]), dtype=x.dtype)
+    for b in range(nb):
+        for h in range(Hkv):
+            out[b, h] = x[b, h][keep_idx[b, h]]
+    return out
+
+
+def evict_step(q, k, v, n_ctx: int, M: int, reduce: int = REDUCE_MAX, scale=None,
+               k_bits=None, v_bits=None):
+    """One eviction step (Alg. 1 phase A3): score, keep top M, compact K and V.
+
+    The selection is taken on the scores rounded to float32, the precision of
+    the score buffer that the selection reads.  k_bits / v_bits, if given, are
+    the raw bit patterns to gather instead of k / v.
+    Returns (scores float64, keep_idx int32, K', V').
+    """
+    s = score(q, k, n_ctx, reduce, scale)
+    idx = topk(s.astype(np.float32), M)
+    kk = compact(k if k_bits is None else k_bits, idx)
+    vv = compact(v if v_bits is None else v_bits, idx)
+    return s, idx, kk, vv
