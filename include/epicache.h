@@ -1,0 +1,127 @@
+/*
+ * epicache.h - C ABI of the MI355X (gfx950) eviction-step library.
+ *
+ * One eviction step of EpiCache's block-wise prefill: after a block of M_block
+ * tokens has been appended to a cache of at most M entries, the patched-prompt
+ * queries of each episode score every context token by the attention it
+ * receives, each KV head keeps its top M tokens and the K/V cache is compacted
+ * back to M rows (paper Sec. 2.2, Sec. 2.3 Eq. 1, Sec. 3.1 Stage 2, Alg. 1
+ * phase A3, App. A.3).  All episodes (and, if the caller folds them into the
+ * batch axis, all layers) are processed by one call.
+ *
+ * Conventions that hold for every entry point
+ *   - `params` and `bytes_out` are HOST pointers.  Every other pointer is a
+ *     DEVICE pointer, 16-byte aligned, owned by the caller.  The library never
+ *     allocates, frees or retains device memory and keeps no state between
+ *     calls.
+ *   - A call validates its arguments on the host, enqueues its kernels on
+ *     `hip_stream` (a hipStream_t; NULL = the default stream) and returns
+ *     without synchronising.  The return value is an epicache_status; it
+ *     covers validation and launch errors only.  On a validation error nothing
+ *     has been enqueued.
+ *   - Layouts are row-major with the innermost head_dim axis contiguous:
+ *       Q      [n_batch, n_q_heads,  patch_len, head_dim]   (strides q_stride_*)
+ *       K, V   [n_batch, n_kv_heads, capacity,  head_dim]   (strides kv_stride_*)
+ *       scores [n_batch, n_kv_heads, N]            float32, dense
+ *       keep   [n_batch, n_kv_heads, n_keep]       int32,   dense
+ *     with N = n_cached + n_block context rows and n_keep = min(budget, N).
+ *     Strides are in elements and must be multiples of 8; K and V share strides.
+ *     Query head hq belongs to KV head hq / (n_q_heads / n_kv_heads).
+ *   - Supported: dtype f32 or bf16; head_dim a multiple of 8, 8..256;
+ *     N <= 2^24; patch_len * (n_q_heads / n_kv_heads) <= 4096; n_batch * n_kv_heads <= 65535.
+ *     Anything else returns EPICACHE_ERR_UNSUPPORTED.
+ *   - Calls that use the same workspace or the same K/V buffers must be ordered
+ *     by the caller (same stream or events).
+ */
+#ifndef EPICACHE_H
+#define EPICACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EPICACHE_API __attribute__((visibility("default")))
+
+typedef enum {
+  EPICACHE_OK = 0,
+  EPICACHE_ERR_INVALID_ARG = 1,        /* null pointer, non-positive size, bad enum, bad stride */
+  EPICACHE_ERR_UNSUPPORTED = 2,        /* valid request outside the supported envelope         */
+  EPICACHE_ERR_WORKSPACE_TOO_SMALL = 3,
+  EPICACHE_ERR_DEVICE = 4              /* a HIP call failed; hipGetLastError has the detail     */
+} epicache_status;
+
+typedef enum { EPICACHE_DTYPE_F32 = 0, EPICACHE_DTYPE_BF16 = 1 } epicache_dtype;
+
+typedef enum {
+  EPICACHE_REDUCE_MAX = 0, /* Eq. 1: s_i = max over the scoring queries of Attn(x_t -> x_i) */
+  EPICACHE_REDUCE_SUM = 1  /* s_i = sum over the scoring queries (attention mass)           */
+} epicache_reduce;
+
+typedef struct epicache_params {
+  uint32_t struct_size;   /* sizeof(epicache_params), checked                                 */
+  int32_t n_batch;        /* E episodes, or L*E when layers are folded in                     */
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                                     */
+  int32_t n_kv_heads;     /* H of the paper                                                   */
+  int32_t head_dim;       /* d                                                                */
+  int32_t n_cached;       /* rows [0, n_cached): cache kept by the previous step, >= 0        */
+  int32_t n_block;        /* rows [n_cached, n_cached+n_block): the new block, >= 0; N >= 1   */
+  int32_t budget;         /* M >= 1 (Sec. 2.1)                                                */
+  int32_t patch_len;      /* p >= 1 scoring queries per query head (Sec. 2.3)                 */
+  int32_t dtype;          /* epicache_dtype of Q, K, V                                        */
+  int32_t reduce;         /* epicache_reduce over the G*p rows that vote for one KV head      */
+  float softmax_scale;    /* logit scale; 0 selects 1/sqrt(head_dim)                          */
+  int64_t q_stride_b, q_stride_h, q_stride_t;    /* Q strides: batch, head, token             */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_t; /* K/V strides; capacity = rows per head     */
+} epicache_params;
+
+/* Bytes of device workspace that any of the calls below needs for `params`
+ * (the maximum over them, reached by epicache_evict_step with both optional
+ * outputs NULL).  Pure host computation. */
+EPICACHE_API int epicache_workspace_size(const epicache_params* params, size_t* bytes_out);
+
+/* Sec. 2.3, Eq. 1.  For every batch item b, KV head h and context row i < N:
+ * softmax over the N context keys of scale * q.k for each of the G*p query
+ * rows of the group, reduced over those rows with `reduce`.
+ * In: q, k (read only).  Out: scores [n_batch, n_kv_heads, N] float32.
+ * Arithmetic: products and sums in fp32, exponentials in fp32. */
+EPICACHE_API int epicache_score(const epicache_params* params, const void* q, const void* k,
+                   float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Sec. 3.1 Stage 2 / Alg. 1 phase A3 ("retain the top M tokens").  For every
+ * (b, h): the n_keep = min(budget, N) rows with the largest score, written in
+ * ascending row order.  Equal scores: the lower row index wins.  Scores are
+ * ordered as IEEE-754 totals (-0 < +0, NaN with the sign bit clear above +inf).
+ * In: scores [n_batch, n_kv_heads, N].  Out: keep_idx [n_batch, n_kv_heads, n_keep]. */
+EPICACHE_API int epicache_topk(const epicache_params* params, const float* scores, int32_t* keep_idx,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Sec. 2.2 / App. A.3 ("reduce the cache back to M").  In place, for every
+ * (b, h) and j < n_keep:  K[b,h,j,:] = K[b,h,keep_idx[b,h,j],:], same for V.
+ * keep_idx must be strictly ascending within [0, N) (as epicache_topk writes
+ * it); this is not checked on the device.  Rows >= n_keep are left as they
+ * are.  Pure copy, bit exact. */
+EPICACHE_API int epicache_compact(const epicache_params* params, const int32_t* keep_idx, void* k, void* v,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Alg. 1 phase A3, one block: score -> topk -> compact on one stream, no host
+ * synchronisation in between.  scores_opt / keep_idx_opt may be NULL (then the
+ * intermediates live in the workspace).  If N <= budget nothing is evicted:
+ * keep_idx_opt, if given, is 0..N-1, scores_opt, if given, is still computed,
+ * K and V are untouched. */
+EPICACHE_API int epicache_evict_step(const epicache_params* params, const void* q, void* k, void* v,
+                        float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/* Static, NUL-terminated description of an epicache_status value. */
+EPICACHE_API const char* epicache_status_string(int status);
+
+/* Library version, "major.minor.patch". */
+EPICACHE_API const char* epicache_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPICACHE_H */

@@ -1,0 +1,156 @@
+"""ctypes binding of libepicache.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in include/epicache.h
+and takes torch tensors that live on the GPU; the tensors supply device
+pointers and strides, torch supplies the current HIP stream.  Nothing is
+computed here and there is no fallback: if the library is missing, loading
+fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libepicache.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_DEVICE = range(5)
+DTYPE_F32, DTYPE_BF16 = 0, 1
+REDUCE_MAX, REDUCE_SUM = 0, 1
+
+ENTRY_POINTS = (
+    "epicache_workspace_size", "epicache_score", "epicache_topk", "epicache_compact",
+    "epicache_evict_step", "epicache_status_string", "epicache_version",
+)
+
+
+class Params(ctypes.Structure):
+    """struct epicache_params"""
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("n_batch", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("n_cached", ctypes.c_int32),
+        ("n_block", ctypes.c_int32),
+        ("budget", ctypes.c_int32),
+        ("patch_len", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("reduce", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+        ("q_stride_b", ctypes.c_int64),
+        ("q_stride_h", ctypes.c_int64),
+        ("q_stride_t", ctypes.c_int64),
+        ("kv_stride_b", ctypes.c_int64),
+        ("kv_stride_h", ctypes.c_int64),
+        ("kv_stride_t", ctypes.c_int64),
+    ]
+
+
+class EpicacheError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library built in-tree.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2509_17396_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    pp = ctypes.POINTER(Params)
+    lib.epicache_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.epicache_score.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_topk.argtypes = [pp, vp, vp, vp, sz, vp]
+    lib.epicache_compact.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in ENTRY_POINTS[:5]:
+        getattr(lib, name).restype = i32
+    lib.epicache_status_string.argtypes = [i32]
+    lib.epicache_status_string.restype = ctypes.c_char_p
+    lib.epicache_version.argtypes = []
+    lib.epicache_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().epicache_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return load().epicache_version().decode()
+
+
+def make_params(q: torch.Tensor, k: torch.Tensor, n_cached: int, n_block: int, budget: int,
+                reduce: int = REDUCE_MAX, softmax_scale: float = 0.0) -> Params:
+    """Fill epicache_params from Q [nb,Hq,p,d] and K [nb,Hkv,C,d] (shapes and strides only)."""
+    nb, Hq, p, d = q.shape
+    assert q.dtype == k.dtype and q.stride(3) == 1 and k.stride(3) == 1
+    dtype = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}[q.dtype]
+    return Params(ctypes.sizeof(Params), nb, Hq, k.shape[1], d, n_cached, n_block, budget, p, dtype,
+                  reduce, softmax_scale, q.stride(0), q.stride(1), q.stride(2),
+                  k.stride(0), k.stride(1), k.stride(2))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise EpicacheError(status, where)
+
+
+def epicache_workspace_size(params: Params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().epicache_workspace_size(ctypes.byref(params), ctypes.byref(out)),
+           "epicache_workspace_size")
+    return out.value
+
+
+def alloc_workspace(params: Params, device="cuda") -> torch.Tensor:
+    return torch.empty(max(epicache_workspace_size(params), 256), dtype=torch.uint8, device=device)
+
+
+def epicache_score(params: Params, q, k, scores, workspace) -> None:
+    _check(load().epicache_score(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(scores),
+                                 _ptr(workspace), workspace.numel(), _stream()), "epicache_score")
+
+
+def epicache_topk(params: Params, scores, keep_idx, workspace=None) -> None:
+    _check(load().epicache_topk(ctypes.byref(params), _ptr(scores), _ptr(keep_idx), _ptr(workspace),
+                                0 if workspace is None else workspace.numel(), _stream()),
+           "epicache_topk")
+
+
+def epicache_compact(params: Params, keep_idx, k, v, workspace=None) -> None:
+    _check(load().epicache_compact(ctypes.byref(params), _ptr(keep_idx), _ptr(k), _ptr(v),
+                                   _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                   _stream()), "epicache_compact")
+
+
+def epicache_evict_step(params: Params, q, k, v, workspace, scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
+                                      _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
+           "epicache_evict_step")

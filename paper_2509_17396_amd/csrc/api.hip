@@ -1,0 +1,208 @@
+// C ABI of libepicache: host-side validation, workspace layout and the launch
+// sequence of one eviction step (paper Alg. 1 phase A3).  No kernel lives here.
+#include <math.h>
+#include <string.h>
+
+#include "epicache_internal.h"
+
+namespace epicache {
+
+static size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int make_plan(const epicache_params* prm, Plan* out) {
+  if (!prm || !out) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->struct_size != sizeof(epicache_params)) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->n_batch < 1 || prm->n_q_heads < 1 || prm->n_kv_heads < 1 || prm->head_dim < 1 ||
+      prm->n_cached < 0 || prm->n_block < 0 || prm->budget < 1 || prm->patch_len < 1)
+    return EPICACHE_ERR_INVALID_ARG;
+  if (prm->n_q_heads % prm->n_kv_heads != 0) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->dtype != EPICACHE_DTYPE_F32 && prm->dtype != EPICACHE_DTYPE_BF16)
+    return EPICACHE_ERR_INVALID_ARG;
+  if (prm->reduce != EPICACHE_REDUCE_MAX && prm->reduce != EPICACHE_REDUCE_SUM)
+    return EPICACHE_ERR_INVALID_ARG;
+  if (!(prm->softmax_scale >= 0.0f) || isinf(prm->softmax_scale)) return EPICACHE_ERR_INVALID_ARG;
+  const int64_t N64 = (int64_t)prm->n_cached + prm->n_block;
+  if (N64 < 1) return EPICACHE_ERR_INVALID_ARG;
+
+  Plan pl;
+  memset(&pl, 0, sizeof(pl));
+  pl.nb = prm->n_batch;
+  pl.Hq = prm->n_q_heads;
+  pl.Hkv = prm->n_kv_heads;
+  pl.G = pl.Hq / pl.Hkv;
+  pl.d = prm->head_dim;
+  pl.p = prm->patch_len;
+  pl.M = prm->budget;
+  pl.dtype = prm->dtype;
+  pl.reduce = prm->reduce;
+  pl.elem = prm->dtype == EPICACHE_DTYPE_F32 ? 4 : 2;
+  pl.qsb = prm->q_stride_b, pl.qsh = prm->q_stride_h, pl.qst = prm->q_stride_t;
+  pl.ksb = prm->kv_stride_b, pl.ksh = prm->kv_stride_h, pl.kst = prm->kv_stride_t;
+
+  // strides: innermost axis contiguous, rows must not overlap, 16-byte friendly
+  const int64_t strides[6] = {pl.qsb, pl.qsh, pl.qst, pl.ksb, pl.ksh, pl.kst};
+  for (int i = 0; i < 6; i++)
+    if (strides[i] < 0 || strides[i] % 8 != 0) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.qst < pl.d || pl.kst < pl.d) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.qsh < pl.qst * (int64_t)(pl.p - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.ksh < pl.kst * (N64 - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.nb > 1 && (pl.qsb < pl.qsh * (int64_t)(pl.Hq - 1) + pl.qst * (int64_t)(pl.p - 1) + pl.d ||
+                    pl.ksb < pl.ksh * (int64_t)(pl.Hkv - 1) + pl.kst * (N64 - 1) + pl.d))
+    return EPICACHE_ERR_INVALID_ARG;
+
+  // supported envelope
+  if (pl.d % 8 != 0 || pl.d < 8 || pl.d > 256) return EPICACHE_ERR_UNSUPPORTED;
+  if (N64 > (1 << 24)) return EPICACHE_ERR_UNSUPPORTED;
+  const int64_t R64 = (int64_t)pl.G * pl.p;
+  if (R64 > 4096) return EPICACHE_ERR_UNSUPPORTED;
+  const int64_t nbh = (int64_t)pl.nb * pl.Hkv;
+  if (nbh > 65535) return EPICACHE_ERR_UNSUPPORTED;
+
+  pl.N = (int)N64;
+  pl.R = (int)R64;
+  pl.Rpad = (pl.R + 63) / 64 * 64;
+  pl.n_keep = pl.M < pl.N ? pl.M : pl.N;
+  const float scale = prm->softmax_scale > 0.0f ? prm->softmax_scale : 1.0f / sqrtf((float)pl.d);
+  pl.c2 = scale * 1.44269504088896340736f;
+
+  pl.use_mfma = (pl.dtype == EPICACHE_DTYPE_BF16 && (pl.d == 128 || pl.d == 64)) ? 1 : 0;
+  if (pl.use_mfma) {
+    const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
+    const int64_t base = nbh * ((pl.R + kRowsPerWG - 1) / kRowsPerWG);
+    int64_t want = (1024 + base - 1) / base;       // enough workgroups to fill 256 CUs
+    int64_t cap = tiles / 4 > 1 ? tiles / 4 : 1;   // at least 4 key tiles per workgroup
+    if (want > cap) want = cap;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    pl.tiles_per_split = (int)((tiles + want - 1) / want);
+    pl.n_splits = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
+  } else {
+    pl.n_splits = 1;
+    pl.tiles_per_split = 0;
+  }
+
+  size_t off = 0;
+  pl.off_stats = off;
+  off += align256((size_t)nbh * pl.n_splits * pl.Rpad * sizeof(float2));
+  pl.off_scores = off;
+  off += align256((size_t)nbh * pl.N * sizeof(float));
+  pl.off_keep = off;
+  off += align256((size_t)nbh * pl.n_keep * sizeof(int32_t));
+  pl.ws_total = off;
+  *out = pl;
+  return EPICACHE_OK;
+}
+
+static bool misaligned(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
+
+static int run_score(const Plan& pl, const void* q, const void* k, float* scores, char* ws,
+                     hipStream_t stream) {
+  float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
+  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, stream)
+                             : launch_score_generic(pl, q, k, scores, stats, stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+}  // namespace epicache
+
+using namespace epicache;
+
+extern "C" {
+
+int epicache_workspace_size(const epicache_params* params, size_t* bytes_out) {
+  if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = pl.ws_total;
+  return EPICACHE_OK;
+}
+
+int epicache_score(const epicache_params* params, const void* q, const void* k, float* scores,
+                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(scores) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  return run_score(pl, q, k, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
+}
+
+int epicache_topk(const epicache_params* params, const float* scores, int32_t* keep_idx,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;  // the selection keeps its state on chip
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!scores || !keep_idx) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(scores) || misaligned(keep_idx)) return EPICACHE_ERR_INVALID_ARG;
+  hipError_t e = launch_topk(pl, scores, keep_idx, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_compact(const epicache_params* params, const int32_t* keep_idx, void* k, void* v,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;  // in-place gather, no staging buffer
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!keep_idx || !k || !v) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(keep_idx) || misaligned(k) || misaligned(v)) return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  hipError_t e = launch_compact(pl, keep_idx, k, v, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_evict_step(const epicache_params* params, const void* q, void* k, void* v,
+                        float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) ||
+      misaligned(scores_opt) || misaligned(keep_idx_opt))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  const size_t need = !scores_opt ? (!keep_idx_opt ? pl.ws_total : pl.off_keep) :
+                      (!keep_idx_opt ? pl.ws_total : pl.off_scores);
+  if (workspace_bytes < need) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
+  int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
+
+  if (pl.N <= pl.M) {  // nothing to evict: the cache is still filling up (App. A.3)
+    if (scores_opt) {
+      st = run_score(pl, q, k, scores, ws, stream);
+      if (st != EPICACHE_OK) return st;
+    }
+    if (keep_idx_opt && launch_iota_keep(pl, keep, stream) != hipSuccess)
+      return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  }
+  st = run_score(pl, q, k, scores, ws, stream);
+  if (st != EPICACHE_OK) return st;
+  if (launch_topk(pl, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  if (launch_compact(pl, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
+}
+
+const char* epicache_status_string(int status) {
+  switch (status) {
+    case EPICACHE_OK: return "ok";
+    case EPICACHE_ERR_INVALID_ARG: return "invalid argument";
+    case EPICACHE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case EPICACHE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case EPICACHE_ERR_DEVICE: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* epicache_version(void) { return "0.1.0"; }
+
+}  // extern "C"

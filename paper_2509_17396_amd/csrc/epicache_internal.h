@@ -1,0 +1,49 @@
+// Internal declarations shared by the HIP translation units of libepicache.
+// Not part of the C ABI (see include/epicache.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "epicache.h"
+
+namespace epicache {
+
+// Everything the launchers need, derived once on the host from epicache_params.
+struct Plan {
+  int nb, Hq, Hkv, G, d, p;
+  int N;        // context rows scored: n_cached + n_block
+  int R;        // rows that vote for one KV head: G * p
+  int Rpad;     // R rounded up to 64
+  int M;        // budget
+  int n_keep;   // min(M, N)
+  int dtype, reduce;
+  int elem;     // bytes per element of Q/K/V
+  float c2;     // softmax scale * log2(e): logits are handled in base 2
+  int64_t qsb, qsh, qst, ksb, ksh, kst;  // strides in elements
+  // score kernels
+  int use_mfma;     // bf16 MFMA path (d == 64 or 128), else the generic path
+  int n_splits;     // key splits of the row-statistics pass
+  int tiles_per_split;
+  // workspace layout (byte offsets, 256-aligned)
+  size_t off_stats, off_scores, off_keep, ws_total;
+};
+
+constexpr int kKeyTile = 64;     // keys staged per LDS tile in the statistics pass
+constexpr int kRowsPerWG = 256;  // query rows per workgroup in the statistics pass
+constexpr int kKeysPerWG = 256;  // keys per workgroup in the reduction pass
+
+int make_plan(const epicache_params* prm, Plan* out);
+
+// Each launcher enqueues on `stream` and returns a hipError_t.
+hipError_t launch_score_generic(const Plan& pl, const void* q, const void* k, float* scores,
+                                float2* stats, hipStream_t stream);
+hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float* scores,
+                             float2* stats, hipStream_t stream);
+hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipStream_t stream);
+hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);
+hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
+                          hipStream_t stream);
+
+}  // namespace epicache

@@ -1,0 +1,103 @@
+"""The C-ABI library: it loads, exports what include/epicache.h declares, and its
+host-side validation returns the documented status codes.  No GPU needed: every
+call here fails validation before anything is enqueued (or is pure host code)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2509_17396_amd import binding as ep
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _params(**kw):
+    q = torch.empty(2, 8, 16, 128, dtype=torch.bfloat16)
+    k = torch.empty(2, 2, 640, 128, dtype=torch.bfloat16)
+    prm = ep.make_params(q, k, n_cached=512, n_block=128, budget=512, reduce=ep.REDUCE_SUM)
+    for name, val in kw.items():
+        setattr(prm, name, val)
+    return prm
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "epicache.h")).read()
+    declared = re.findall(r"EPICACHE_API\s+[\w\s\*]+?\b(epicache_\w+)\s*\(", header)
+    assert set(declared) == set(ep.ENTRY_POINTS) and len(declared) == len(ep.ENTRY_POINTS)
+    lib = ep.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert re.fullmatch(r"\d+\.\d+\.\d+", ep.version())
+
+
+def test_params_struct_matches_header_layout():
+    assert ctypes.sizeof(ep.Params) == 4 * 12 + 8 * 6
+    assert ep.Params.q_stride_b.offset == 48
+
+
+def test_status_strings():
+    seen = {ep.status_string(s) for s in range(5)}
+    assert len(seen) == 5 and ep.status_string(99) == "unknown status"
+
+
+def test_workspace_size_is_host_only_and_monotone():
+    small = ep.epicache_workspace_size(_params())
+    assert small > 0 and small % 256 == 0
+    assert ep.epicache_workspace_size(_params(patch_len=8, q_stride_h=8 * 128)) <= small
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("struct_size", 4, ep.ERR_INVALID_ARG),
+    ("n_batch", 0, ep.ERR_INVALID_ARG),
+    ("budget", 0, ep.ERR_INVALID_ARG),
+    ("patch_len", 0, ep.ERR_INVALID_ARG),
+    ("n_kv_heads", 3, ep.ERR_INVALID_ARG),       # 8 % 3 != 0
+    ("dtype", 7, ep.ERR_INVALID_ARG),
+    ("reduce", 2, ep.ERR_INVALID_ARG),
+    ("softmax_scale", -1.0, ep.ERR_INVALID_ARG),
+    ("softmax_scale", float("nan"), ep.ERR_INVALID_ARG),
+    ("n_block", -600, ep.ERR_INVALID_ARG),
+    ("kv_stride_t", 64, ep.ERR_INVALID_ARG),     # rows would overlap
+    ("kv_stride_t", 132, ep.ERR_INVALID_ARG),    # not a multiple of 8
+    ("kv_stride_h", 1000, ep.ERR_INVALID_ARG),   # capacity below N
+    ("head_dim", 12, ep.ERR_UNSUPPORTED),
+    ("n_cached", (1 << 24) + 8, ep.ERR_INVALID_ARG),  # exceeds the capacity the strides imply
+])
+def test_bad_params_are_rejected_before_any_launch(field, value, status):
+    prm = _params(**{field: value})
+    out = ctypes.c_size_t(0)
+    lib = ep.load()
+    assert lib.epicache_workspace_size(ctypes.byref(prm), ctypes.byref(out)) == status
+    # the compute entry points validate params first, with the same result
+    dummy = ctypes.c_void_p(4096)
+    assert lib.epicache_score(ctypes.byref(prm), dummy, dummy, dummy, dummy, 1 << 30, None) == status
+    assert lib.epicache_topk(ctypes.byref(prm), dummy, dummy, None, 0, None) == status
+    assert lib.epicache_compact(ctypes.byref(prm), dummy, dummy, ctypes.c_void_p(8192), None, 0, None) == status
+    assert lib.epicache_evict_step(ctypes.byref(prm), dummy, dummy, ctypes.c_void_p(8192), None, None,
+                                   dummy, 1 << 30, None) == status
+
+
+def test_null_misaligned_and_small_workspace_are_rejected():
+    prm = _params()
+    lib = ep.load()
+    a, b, c = ctypes.c_void_p(4096), ctypes.c_void_p(8192), ctypes.c_void_p(4100)
+    need = ep.epicache_workspace_size(prm)
+    assert lib.epicache_workspace_size(ctypes.byref(prm), None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_workspace_size(None, ctypes.byref(ctypes.c_size_t())) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score(ctypes.byref(prm), None, a, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score(ctypes.byref(prm), a, c, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score(ctypes.byref(prm), a, a, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_topk(ctypes.byref(prm), a, None, None, 0, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_compact(ctypes.byref(prm), a, a, a, None, 0, None) == ep.ERR_INVALID_ARG  # K is V
+    assert lib.epicache_compact(ctypes.byref(prm), a, a, None, None, 0, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_evict_step(ctypes.byref(prm), a, a, b, None, None, a, need - 1, None) == \
+        ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_evict_step(ctypes.byref(prm), a, a, a, None, None, a, need, None) == ep.ERR_INVALID_ARG
+
+
+def test_binding_raises_with_status():
+    with pytest.raises(ep.EpicacheError) as ei:
+        ep.epicache_workspace_size(_params(budget=-3))
+    assert ei.value.status == ep.ERR_INVALID_ARG

@@ -1,0 +1,300 @@
+"""GPU parity: every entry point of libepicache, called through the C ABI, against the
+CPU oracle on the same seeded inputs.  Sizes here are ones the oracle finishes in
+seconds; they span several tiles, ragged tails and the degenerate cases."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import epicache_oracle as orc
+from paper_2509_17396_amd import binding as ep
+from paper_2509_17396_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def wl(name, **kw):
+    return synth.WORKLOADS[name].scaled(**kw)
+
+
+def gpu_score(q, k, N, M, reduce, scale=0.0):
+    prm = ep.make_params(q, k, n_cached=min(M, N), n_block=N - min(M, N), budget=M, reduce=reduce,
+                         softmax_scale=scale)
+    ws = ep.alloc_workspace(prm)
+    scores = torch.full((q.shape[0], k.shape[1], N), float("nan"), dtype=torch.float32, device=DEV)
+    ep.epicache_score(prm, q, k, scores, ws)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy()
+
+
+# ------------------------------------------------------------------- score
+
+SCORE_CASES = [
+    # name, base workload, overrides, n_ctx, capacity
+    ("tiny_fp32_cfg1", "tiny", {}, None, None),
+    ("fp32_ragged", "tiny", dict(E=2, Hq=6, Hkv=2, p=5, d=40), 203, 230),
+    ("fp32_one_key", "tiny", dict(p=3), 1, 4),
+    ("bf16_mfma_d128_small", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=64), 640, None),
+    ("bf16_mfma_d128_ragged_rows_keys", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=37), 1000 + 37, 1100),
+    ("bf16_mfma_d128_R_above_256", "llama31_8b", dict(E=1, Hq=8, Hkv=2, p=100), 777, None),
+    ("bf16_mfma_d128_few_keys", "llama32_3b", dict(E=1, Hq=4, Hkv=4, p=16), 5, 8),
+    ("bf16_mfma_d64", "llama32_3b", dict(E=2, Hq=4, Hkv=2, p=48, d=64), 333, None),
+    ("bf16_mfma_student_t", "stress", dict(E=1, Hq=8, Hkv=2, p=64), 2048 + 13, None),
+    ("bf16_mfma_topics_G7", "qwen25_7b", dict(E=2, Hq=14, Hkv=2, p=32), 1536, None),
+    ("bf16_generic_d96", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=9, d=96), 150, None),
+]
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+@pytest.mark.parametrize("case", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
+def test_score_matches_oracle(case, reduce):
+    name, base, over, n_ctx, cap = case
+    w = wl(base, **over)
+    N = w.N if n_ctx is None else n_ctx
+    say(f"score {name} reduce={reduce} N={N} R={w.R} d={w.d} {w.dtype}")
+    q, k, _ = synth.make_layer(w, layer=0, n_ctx=N, capacity=cap)
+    got = gpu_score(q.to(DEV), k.to(DEV), N, w.M, reduce)
+    qq, kk = pu.oracle_inputs(q, k)
+    want = orc.score(qq, kk, N, reduce)
+    worst = pu.assert_scores_close(got, want, pu.rtol_for(q.dtype), name)
+    say(f"  max rel err {worst:.3e}")
+
+
+def test_score_explicit_scale_and_strided_views():
+    """Non-default softmax scale; Q and K are views into larger buffers (strides != dense)."""
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=24)
+    N, cap = 300, 512
+    say("score strided views + explicit scale")
+    q, k, _ = synth.make_layer(w, layer=3, n_ctx=N, capacity=cap)
+    qbig = torch.zeros(2, 6, 40, 128 + 64, dtype=q.dtype, device=DEV)
+    kbig = torch.zeros(2, 2, cap + 5, 128 + 8, dtype=k.dtype, device=DEV)
+    qv = qbig[:, :, 8:8 + 24, 64:]       # data_ptr offset 8*192+64 elements: 16-byte aligned
+    kv = kbig[:, :, 5:, 8:]
+    qv.copy_(q), kv.copy_(k)
+    for reduce in (orc.REDUCE_MAX, orc.REDUCE_SUM):
+        got = gpu_score(qv, kv, N, 128, reduce, scale=0.05)
+        want = orc.score(*pu.oracle_inputs(q, k), N, reduce, scale=0.05)
+        pu.assert_scores_close(got, want, pu.RTOL_BF16, "strided")
+
+
+def test_score_mfma_agrees_with_generic_kernel_closely():
+    """Same bf16 inputs through the MFMA path (d=128) and, zero-padded to d=136, through the
+    generic fp32-FMA path: both must sit within the tolerance of the oracle, and of each other."""
+    w = wl("llama32_3b", E=1, Hq=6, Hkv=2, p=32)
+    N = 900
+    say("score mfma vs generic")
+    q, k, _ = synth.make_layer(w, layer=1, n_ctx=N)
+    qp = torch.nn.functional.pad(q, (0, 8)).contiguous()
+    kp = torch.nn.functional.pad(k, (0, 8)).contiguous()
+    scale = 1.0 / 128 ** 0.5
+    a = gpu_score(q.to(DEV), k.to(DEV), N, 512, orc.REDUCE_SUM, scale)
+    b = gpu_score(qp.to(DEV), kp.to(DEV), N, 512, orc.REDUCE_SUM, scale)
+    want = orc.score(*pu.oracle_inputs(q, k), N, orc.REDUCE_SUM, scale)
+    pu.assert_scores_close(a, want, pu.RTOL_BF16, "mfma")
+    pu.assert_scores_close(b, want, pu.RTOL_BF16, "generic")
+    np.testing.assert_allclose(a, b, rtol=1e-3, atol=pu.ATOL)
+
+
+# -------------------------------------------------------------------- topk
+
+def gpu_topk(scores_np, M):
+    nb, H, N = scores_np.shape
+    s = torch.from_numpy(scores_np).to(DEV)
+    q = torch.empty(nb, H, 1, 8, dtype=torch.float32, device=DEV)   # shapes only
+    k = torch.empty(nb, H, N, 8, dtype=torch.float32, device=DEV)
+    prm = ep.make_params(q, k, n_cached=0, n_block=N, budget=M)
+    keep = torch.full((nb, H, min(M, N)), -7, dtype=torch.int32, device=DEV)
+    ep.epicache_topk(prm, s, keep)
+    torch.cuda.synchronize()
+    return keep.cpu().numpy()
+
+
+TOPK_SIZES = [(1, 1), (7, 3), (64, 1), (65, 64), (1000, 333), (1024, 1023), (1025, 512), (4096, 2048),
+              (5000, 2500), (8192, 4096), (10240, 8192), (16385, 9000), (24576, 16384), (32768, 100),
+              (40000, 20000), (70001, 35000)]
+
+
+@pytest.mark.parametrize("N,M", TOPK_SIZES, ids=[f"N{n}_M{m}" for n, m in TOPK_SIZES])
+@pytest.mark.parametrize("kind", ["uniform", "ties", "underflow", "signed"])
+def test_topk_identical_to_oracle(N, M, kind):
+    say(f"topk N={N} M={M} {kind}")
+    rng = np.random.default_rng(N * 7919 + M)
+    if kind == "uniform":
+        s = rng.random((2, 3, N), dtype=np.float32)
+    elif kind == "ties":            # few distinct values: the threshold class is large
+        s = (rng.integers(0, 5, (2, 3, N)) / 8).astype(np.float32)
+    elif kind == "underflow":       # most weights flushed to exactly 0, as with near one-hot rows
+        s = np.where(rng.random((2, 3, N)) < 0.9, 0.0, rng.random((2, 3, N)) * 1e-30).astype(np.float32)
+    else:                           # arbitrary floats incl. negatives, -0.0 and infinities
+        s = rng.standard_normal((2, 3, N)).astype(np.float32)
+        s[0, 0, : min(N, 4)] = np.array([-0.0, 0.0, np.inf, -np.inf], np.float32)[: min(N, 4)]
+    got = gpu_topk(s, M)
+    if kind == "signed":
+        # the oracle negates scores to sort; -0.0 and +0.0 compare equal there, so pin the
+        # IEEE total order of the library by replacing -0.0 with a value just below +0.0
+        s = s.copy()
+        s[np.signbit(s) & (s == 0)] = -1e-45
+    want = orc.topk(s, M)
+    pu.assert_keep_valid(got, N, min(M, N), kind)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_topk_all_equal_keeps_the_oldest_and_no_eviction_is_identity():
+    s = np.full((1, 2, 3000), 0.125, np.float32)
+    np.testing.assert_array_equal(gpu_topk(s, 1200), np.tile(np.arange(1200, dtype=np.int32), (1, 2, 1)))
+    np.testing.assert_array_equal(gpu_topk(s, 3000), np.tile(np.arange(3000, dtype=np.int32), (1, 2, 1)))
+    np.testing.assert_array_equal(gpu_topk(s, 5000), np.tile(np.arange(3000, dtype=np.int32), (1, 2, 1)))
+
+
+# ----------------------------------------------------------------- compact
+
+def gpu_compact(k, v, keep_np, N, M):
+    kd, vd = k.to(DEV).clone(), v.to(DEV).clone()
+    q = torch.empty(k.shape[0], k.shape[1], 1, k.shape[3], dtype=k.dtype, device=DEV)
+    prm = ep.make_params(q, kd, n_cached=0, n_block=N, budget=M)
+    ep.epicache_compact(prm, torch.from_numpy(keep_np).to(DEV), kd, vd)
+    torch.cuda.synchronize()
+    return kd.cpu(), vd.cpu()
+
+
+COMPACT_CASES = [
+    # nb, H, N, M, d, dtype, kept prefix already in place
+    (1, 2, 384, 256, 64, torch.float32, 0),
+    (2, 3, 1000, 417, 128, torch.bfloat16, 0),
+    (3, 2, 4096, 2048, 128, torch.bfloat16, 700),
+    (1, 1, 129, 128, 8, torch.bfloat16, 0),
+    (2, 2, 777, 300, 96, torch.bfloat16, 0),
+    (1, 1, 5000, 4999, 256, torch.float32, 0),
+    (40, 8, 600, 300, 128, torch.bfloat16, 17),     # >= 1024 problems: one slice per row
+]
+
+
+@pytest.mark.parametrize("case", COMPACT_CASES, ids=[f"c{i}" for i in range(len(COMPACT_CASES))])
+def test_compact_bit_exact(case):
+    nb, H, N, M, d, dtype, prefix = case
+    say(f"compact nb={nb} H={H} N={N} M={M} d={d} {dtype} prefix={prefix}")
+    g = torch.Generator().manual_seed(N * 31 + M)
+    cap = N + 3
+    k = torch.randn(nb, H, cap, d, generator=g).to(dtype)
+    v = torch.randn(nb, H, cap, d, generator=g).to(dtype)
+    rng = np.random.default_rng(N + M)
+    keep = np.empty((nb, H, M), np.int32)
+    for b in range(nb):
+        for h in range(H):
+            rest = np.sort(rng.choice(np.arange(prefix, N), M - prefix, replace=False))
+            keep[b, h] = np.concatenate([np.arange(prefix), rest])
+    kd, vd = gpu_compact(k, v, keep, N, M)
+    kb, vb = synth.raw_bits_numpy(k), synth.raw_bits_numpy(v)
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd)[:, :, :M], orc.compact(kb, keep))
+    np.testing.assert_array_equal(synth.raw_bits_numpy(vd)[:, :, :M], orc.compact(vb, keep))
+    # rows beyond the kept ones are left as they were
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd)[:, :, M:], kb[:, :, M:])
+
+
+# -------------------------------------------------------------- evict step
+
+def run_evict_step(w, q, k, v, N, reduce, want_intermediates=True):
+    qd, kd, vd = q.to(DEV), k.to(DEV).clone(), v.to(DEV).clone()
+    n_cached = min(w.M, N)
+    prm = ep.make_params(qd, kd, n_cached=n_cached, n_block=N - n_cached, budget=w.M, reduce=reduce)
+    ws = ep.alloc_workspace(prm)
+    scores = keep = None
+    if want_intermediates:
+        scores = torch.full((qd.shape[0], kd.shape[1], N), float("nan"), dtype=torch.float32, device=DEV)
+        keep = torch.full((qd.shape[0], kd.shape[1], min(w.M, N)), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step(prm, qd, kd, vd, ws, scores, keep)
+    torch.cuda.synchronize()
+    return (None if scores is None else scores.cpu().numpy(),
+            None if keep is None else keep.cpu().numpy(), kd.cpu(), vd.cpu())
+
+
+def check_evict_step(w, q, k, v, N, reduce, what):
+    scores, keep, kd, vd = run_evict_step(w, q, k, v, N, reduce)
+    rtol = pu.rtol_for(q.dtype)
+    qq, kk = pu.oracle_inputs(q, k)
+    kb, vb = synth.raw_bits_numpy(k), synth.raw_bits_numpy(v)
+    o_scores, o_keep, o_k, o_v = orc.evict_step(qq, kk, None, N, w.M, reduce, k_bits=kb, v_bits=vb)
+    pu.assert_scores_close(scores, o_scores, rtol, what)
+    differ = pu.assert_keep_matches(keep, o_scores, w.M, rtol, what)
+    n_keep = min(w.M, N)
+    # compaction is a pure copy: bit exact for the index list the GPU selected ...
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd)[:, :, :n_keep], orc.compact(kb, keep))
+    np.testing.assert_array_equal(synth.raw_bits_numpy(vd)[:, :, :n_keep], orc.compact(vb, keep))
+    # ... and identical to the oracle's cache wherever the kept sets agree
+    same = (keep == o_keep).all(axis=2)
+    assert same.any()
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd)[:, :, :n_keep][same], o_k[same])
+    np.testing.assert_array_equal(synth.raw_bits_numpy(vd)[:, :, :n_keep][same], o_v[same])
+    # the workspace-only variant (no optional outputs) produces the same cache
+    _, _, kd2, vd2 = run_evict_step(w, q, k, v, N, reduce, want_intermediates=False)
+    assert torch.equal(kd2.view(torch.uint8), kd.view(torch.uint8))
+    assert torch.equal(vd2.view(torch.uint8), vd.view(torch.uint8))
+    return differ
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_evict_step_config1_tiny_fp32(reduce):
+    w = wl("tiny")
+    say(f"evict_step tiny reduce={reduce}")
+    q, k, v = synth.make_layer(w)
+    differ = check_evict_step(w, q, k, v, w.N, reduce, "tiny")
+    say(f"  tokens differing inside the band: {differ}")
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_evict_step_config2_one_layer_bf16(reduce):
+    """LLaMA-3.2-3B-shaped layer at full size: E=4, 24/8 heads, M=B=2048, p=64."""
+    w = wl("llama32_3b")
+    say(f"evict_step llama32_3b layer 5 reduce={reduce}")
+    q, k, v = synth.make_layer(w, layer=5)
+    differ = check_evict_step(w, q, k, v, w.N, reduce, "llama32_3b")
+    say(f"  tokens differing inside the band: {differ}")
+
+
+def test_evict_step_when_cache_is_still_filling():
+    """N <= M: nothing is evicted, K/V untouched, keep_idx = 0..N-1, scores still produced."""
+    w = wl("llama32_3b", E=1, Hq=6, Hkv=2, p=16, M=512)
+    N = 300
+    say("evict_step N <= M")
+    q, k, v = synth.make_layer(w, n_ctx=N)
+    scores, keep, kd, vd = run_evict_step(w, q, k, v, N, orc.REDUCE_MAX)
+    np.testing.assert_array_equal(keep, np.tile(np.arange(N, dtype=np.int32), (1, 2, 1)))
+    assert torch.equal(kd.view(torch.int16), k.view(torch.int16)) and torch.equal(vd.view(torch.int16), v.view(torch.int16))
+    pu.assert_scores_close(scores, orc.score(*pu.oracle_inputs(q, k), N, orc.REDUCE_MAX), pu.RTOL_BF16)
+
+
+def test_block_prefill_sweep_with_resynchronisation():
+    """A scaled-down sweep in the shape of config 3: the cache fills, then every step appends a
+    block and evicts back to M.  Each GPU step starts from the oracle's previous cache."""
+    w = wl("llama31_8b", E=2, Hq=8, Hkv=2, p=32, M=512, B=512)
+    steps = 6
+    say("sweep 6 steps M=B=512")
+    cache_k = cache_v = None
+    for step in range(steps):
+        q, bk, bv = synth.make_layer(w, layer=0, step=step, n_ctx=w.B)
+        if cache_k is None:
+            k, v = bk, bv
+        else:
+            k, v = torch.cat([cache_k, bk], dim=2), torch.cat([cache_v, bv], dim=2)
+        N = k.shape[2]
+        assert N <= w.M + w.B
+        scores, keep, kd, vd = run_evict_step(w, q, k, v, N, orc.REDUCE_MAX)
+        o_scores, o_keep, o_k, o_v = orc.evict_step(*pu.oracle_inputs(q, k), None, N, w.M, orc.REDUCE_MAX,
+                                                    k_bits=synth.raw_bits_numpy(k), v_bits=synth.raw_bits_numpy(v))
+        pu.assert_scores_close(scores, o_scores, pu.RTOL_BF16, f"step {step}")
+        pu.assert_keep_matches(keep, o_scores, w.M, pu.RTOL_BF16, f"step {step}")
+        n_keep = min(w.M, N)
+        assert keep.shape[2] == n_keep
+        # resynchronise on the oracle's cache
+        cache_k = torch.from_numpy(o_k.view(np.int16)).view(torch.bfloat16)
+        cache_v = torch.from_numpy(o_v.view(np.int16)).view(torch.bfloat16)
+        assert cache_k.shape[2] == n_keep
