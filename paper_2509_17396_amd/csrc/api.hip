@@ -2,6 +2,7 @@
 // sequence of one eviction step (paper Alg. 1 phase A3).  No kernel lives here.
 #include <math.h>
 #include <string.h>
+#include <stdlib.h>
 
 #include "epicache_internal.h"
 
@@ -68,7 +69,12 @@ int make_plan(const epicache_params* prm, Plan* out) {
   pl.use_mfma = (pl.dtype == EPICACHE_DTYPE_BF16 && (pl.d == 128 || pl.d == 64)) ? 1 : 0;
   if (pl.use_mfma) {
     const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
-    const int64_t base = nbh * ((pl.R + kRowsPerWG - 1) / kRowsPerWG);
+    // rows per workgroup: 256 (4 waves x 64) or 192 (2 waves x 96), whichever pads R less
+    if (pl.R <= 32) pl.stats_rows_per_wg = 32;
+    else if (pl.R <= 64) pl.stats_rows_per_wg = 64;
+    else if (pl.R <= 128) pl.stats_rows_per_wg = 128;
+    else pl.stats_rows_per_wg = ((pl.R + 191) / 192 * 192 < (pl.R + 255) / 256 * 256) ? 192 : 256;
+    const int64_t base = nbh * ((pl.R + pl.stats_rows_per_wg - 1) / pl.stats_rows_per_wg);
     int64_t want = (1024 + base - 1) / base;       // enough workgroups to fill 256 CUs
     int64_t cap = tiles / 4 > 1 ? tiles / 4 : 1;   // at least 4 key tiles per workgroup
     if (want > cap) want = cap;
@@ -81,6 +87,7 @@ int make_plan(const epicache_params* prm, Plan* out) {
     pl.tiles_per_split = 0;
   }
 
+  { const char* e = getenv("EPICACHE_DEBUG"); pl.debug = e ? atoi(e) : 0; }
   size_t off = 0;
   pl.off_stats = off;
   off += align256((size_t)nbh * pl.n_splits * pl.Rpad * sizeof(float2));

@@ -24,14 +24,15 @@ struct Plan {
   int64_t qsb, qsh, qst, ksb, ksh, kst;  // strides in elements
   // score kernels
   int use_mfma;     // bf16 MFMA path (d == 64 or 128), else the generic path
+  int stats_rows_per_wg;  // query rows per workgroup of the row-statistics pass
   int n_splits;     // key splits of the row-statistics pass
   int tiles_per_split;
+  int debug;        // TEMP experiment switches
   // workspace layout (byte offsets, 256-aligned)
   size_t off_stats, off_scores, off_keep, ws_total;
 };
 
 constexpr int kKeyTile = 64;     // keys staged per LDS tile in the statistics pass
-constexpr int kRowsPerWG = 256;  // query rows per workgroup in the statistics pass
 constexpr int kKeysPerWG = 256;  // keys per workgroup in the reduction pass
 
 int make_plan(const epicache_params* prm, Plan* out);

@@ -13,11 +13,23 @@
 // column and 16 keys), pass 2 puts the query rows there (a lane owns one key
 // column and 16 query rows).  Only two lanes (l, l^32) ever need to be combined.
 //
-// Accumulator layout of the 32x32 MFMA used throughout: lane l, value v holds
+// Both passes are bound by the plain ALUs, not by the matrix cores: per logit
+// the softmax costs a multiply-add, an exponential (half rate) and an add or
+// max, about 4 issue slots, against 2 slots' worth of MFMA time.  Each wave
+// therefore software-pipelines by hand: the MFMA chain of tile u+1 is issued
+// one instruction at a time between slices of the softmax arithmetic of tile u.
+//
+// Accumulator layout of the 32x32 MFMA: lane l, value v holds
 //   row = (v / 4) * 8 + (l / 32) * 4 + (v % 4),  column = l % 32.
-// The contraction index each lane feeds is the same for the A and the B
-// operand (16-byte chunk 2*j + l/32 of the head_dim row for MFMA j), which is
-// all the hardware needs for a correct dot product.
+// The contraction index a lane feeds is the same for the A and the B operand
+// (16-byte chunk 2*j + l/32 of the head_dim row for MFMA j), which is all the
+// hardware needs for a correct dot product.
+//
+// Staging: 64-row tiles (keys in pass 1, query rows in pass 2) go from global
+// memory straight into LDS with global_load_lds_dwordx4 (lane l of a wave fills
+// 16-byte slot l of a 1 KiB slab).  Each lane picks the global chunk that makes
+// the LDS image XOR-swizzled, so the ds_read_b128 of the MFMA operands is free
+// of bank conflicts without padding.
 #include "epicache_internal.h"
 
 namespace epicache {
@@ -27,129 +39,302 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef uint16_t bf16_t;  // raw storage
 
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
 __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+__device__ __forceinline__ void fence_sched() { __builtin_amdgcn_sched_barrier(0); }
+// Keeps the computation of x above this point: without it the optimiser sinks a slice of
+// arithmetic down to its first use, past the MFMAs it is meant to fill the shadow of.
+__device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
+
 
 template <int HD>
 struct Tile {
-  static constexpr int kSteps = HD / 16;           // MFMAs per 32x32 output tile
-  static constexpr int kChunks = HD / 8;           // 16-byte chunks per row
-  static constexpr int kRowBytes = HD * 2 + 16;    // LDS row pitch: +16 B keeps ds_read_b128 conflict free
+  static constexpr int kSteps = HD / 16;          // MFMAs per 32x32 output tile
+  static constexpr int kChunks = HD / 8;          // 16-byte chunks per row
+  static constexpr int kRowBytes = HD * 2;
   static constexpr int kTileBytes = 64 * kRowBytes;
-  static constexpr int kLoads = 64 * kChunks / 256;  // 16-byte global loads per thread per 64-row tile
+  static constexpr int kSlabs = kTileBytes / 1024;   // 1 KiB wave-wide direct loads per tile
+  static constexpr int kRowsPerSlab = 1024 / kRowBytes;
+  // XOR swizzle: chunk c of row r sits at position c ^ swz(r)
+  __device__ static __forceinline__ int swz(int r) { return (r / (16 / kChunks)) % kChunks; }
 };
 
-// ------------------------------------------------------------------ pass 1
-template <int HD>
-__global__ __launch_bounds__(256, 2) void score_stats(const bf16_t* __restrict__ q,
-                                                      const bf16_t* __restrict__ k,
-                                                      float2* __restrict__ stats, Plan pl) {
+// 16 bytes per lane, global memory -> LDS without passing through registers: lane l of the wave
+// writes LDS bytes [lds_addr + 16*l, +16).  Issued as inline assembly so that the compiler's
+// wait-count pass does not serialise later ds_reads of the *other* LDS buffer behind these loads;
+// completion is awaited explicitly (wait_vmem) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16_uniform_base(uint32_t lds_addr, const void* base, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(base)
+               : "memory");
+}
+__device__ __forceinline__ void dma16_lane_ptr(uint32_t lds_addr, const void* ptr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(ptr)
+               : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)LDS_PTR(p);
+}
+
+// Staging of one 64-row tile, global -> LDS, by NW waves.  Rows are `stride` bytes apart.
+// Wave w issues the 1 KiB slabs w, w + NW, w + 2*NW, ...; `wave` must be wave-uniform.
+template <int HD, int NW>
+struct Stager {
   using TL = Tile<HD>;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TL::kTileBytes];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  static constexpr int kPer = (TL::kSlabs + NW - 1) / NW;  // direct loads per wave and tile (at most)
+  // byte offset, from the first row of a tile, of the chunk that lane `lane` fetches in load i
+  __device__ static __forceinline__ void offsets(uint32_t (&off)[kPer], int wave, int lane, uint32_t stride) {
+#pragma unroll
+    for (int i = 0; i < kPer; i++) {
+      const int row = (wave + i * NW) * TL::kRowsPerSlab + lane / TL::kChunks;
+      off[i] = row * stride + (((lane % TL::kChunks) ^ TL::swz(row)) * 16);
+    }
+  }
+  // all 64 rows exist: tile base (wave-uniform) + per-lane offsets
+  __device__ static __forceinline__ void run(uint32_t lds_tile, const unsigned char* base,
+                                             const uint32_t (&off)[kPer], int wave) {
+#pragma unroll
+    for (int i = 0; i < kPer; i++)
+      if (TL::kSlabs % NW == 0 || wave + i * NW < TL::kSlabs)
+        dma16_uniform_base(lds_tile + (wave + i * NW) * 1024, base, off[i]);
+  }
+  // general form: `row_ptr(r)` gives the address of row r of the tile (clamping, ragged strides)
+  template <typename RowPtr>
+  __device__ static __forceinline__ void run_rows(uint32_t lds_tile, int wave, int lane, RowPtr row_ptr) {
+#pragma unroll
+    for (int i = 0; i < kPer; i++) {
+      if (TL::kSlabs % NW == 0 || wave + i * NW < TL::kSlabs) {
+        const int row = (wave + i * NW) * TL::kRowsPerSlab + lane / TL::kChunks;
+        dma16_lane_ptr(lds_tile + (wave + i * NW) * 1024,
+                       row_ptr(row) + (((lane % TL::kChunks) ^ TL::swz(row)) * 16));
+      }
+    }
+  }
+};
+
+// MFMA operand fragments of one 32-row sub-tile of a staged tile.
+template <int HD>
+__device__ __forceinline__ void read_frags(bf16x8 (&f)[HD / 16], const unsigned char* lds_tile, int sub,
+                                           int l32, int hi) {
+  using TL = Tile<HD>;
+  const int row = sub * 32 + l32;
+  const unsigned char* base = lds_tile + row * TL::kRowBytes;
+  const int s = TL::swz(row);
+#pragma unroll
+  for (int j = 0; j < TL::kSteps; j++)
+    f[j] = as_frag(*reinterpret_cast<const uint4*>(base + (((2 * j + hi) ^ s) * 16)));
+}
+
+// ------------------------------------------------------------------ pass 1
+// Softmax statistics of the previous accumulator tile, cut into slices that are
+// issued between the MFMAs of the next tile.  16 values = 16 keys of one query row.
+//
+// Sentinels instead of infinities, so that no inf - inf can arise: a row that has
+// seen no key yet has m = kNoMax; masked keys and the filler tile that precedes the
+// first real one hold kMasked < kNoMax, so folding them in leaves (m, D) untouched
+// (their exp2 underflows to exactly 0 and the max does not move).  Raw dot products
+// are assumed to lie above kNoMax.
+struct RowStat {
+  float m, D;  // running max of the raw dot products; running sum of exp2((dot - m) * c2)
+};
+constexpr float kNoMax = -1.5e38f;
+constexpr float kMasked = -3.0e38f;
+
+__device__ __forceinline__ void stats_begin(const f32x16& P, const RowStat& st, float c2, float& mn,
+                                            float& nmc, float& corr) {
+  const float a0 = max3(P[0], P[1], P[2]), a1 = max3(P[3], P[4], P[5]), a2 = max3(P[6], P[7], P[8]);
+  const float a3 = max3(P[9], P[10], P[11]), a4 = max3(P[12], P[13], P[14]);
+  mn = max3(max3(a0, a1, a2), max3(a3, a4, P[15]), st.m);
+  nmc = -mn * c2;
+  corr = ex2((st.m - mn) * c2);  // exactly 1 when the max did not move
+}
+
+__device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, float nmc) {
+  const float e0 = ex2(fmaf(P[4 * g + 0], c2, nmc)), e1 = ex2(fmaf(P[4 * g + 1], c2, nmc));
+  const float e2 = ex2(fmaf(P[4 * g + 2], c2, nmc)), e3 = ex2(fmaf(P[4 * g + 3], c2, nmc));
+  return (e0 + e1) + (e2 + e3);
+}
+
+// acc <- MFMA chain over head_dim (A rows = a-frag rows, B columns = b-frag rows), interleaved
+// with folding P, the tile finished one unit earlier, into its row statistics.
+template <int KS>
+__device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
+                                           const f32x16& P, RowStat& st, float c2) {
+  float mn, nmc, corr, s0, s1, s2, s3;
+  const f32x16 zero = {0};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
+  stats_begin(P, st, c2, mn, nmc, corr);
+  pin(nmc), pin(corr);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
+  s0 = stats_group(P, 0, c2, nmc);
+  pin(s0);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], acc, 0, 0, 0);
+  s1 = stats_group(P, 1, c2, nmc);
+  pin(s1);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], acc, 0, 0, 0);
+  s2 = stats_group(P, 2, c2, nmc);
+  pin(s2);
+  fence_sched();
+  if (KS > 4) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[KS > 4 ? 4 : 0], b[KS > 4 ? 4 : 0], acc, 0, 0, 0);
+    s3 = stats_group(P, 3, c2, nmc);
+    pin(s3);
+    fence_sched();
+#pragma unroll
+    for (int j = 5; j < KS; j++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc, 0, 0, 0);
+  } else {
+    s3 = stats_group(P, 3, c2, nmc);
+  }
+  st.D = fmaf(st.D, corr, (s0 + s1) + (s2 + s3));
+  st.m = mn;
+  fence_sched();
+}
+
+template <int KS>
+__device__ __forceinline__ void mfma_chain(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS]) {
+  const f32x16 zero = {0};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
+#pragma unroll
+  for (int j = 1; j < KS; j++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc, 0, 0, 0);
+}
+
+// fold one finished tile into its row statistics, nothing to overlap with
+__device__ __forceinline__ void stats_fold(const f32x16& P, RowStat& st, float c2) {
+  float mn, nmc, corr;
+  stats_begin(P, st, c2, mn, nmc, corr);
+  const float s = (stats_group(P, 0, c2, nmc) + stats_group(P, 1, c2, nmc)) +
+                  (stats_group(P, 2, c2, nmc) + stats_group(P, 3, c2, nmc));
+  st.D = fmaf(st.D, corr, s);
+  st.m = mn;
+}
+
+// NQ 32-row query sub-tiles per wave, NW waves per workgroup: 32*NQ*NW query rows per workgroup.
+template <int HD, int NQ, int NW>
+__global__ __launch_bounds__(NW * 64, (NQ <= 2 ? 3 : 2)) void score_stats(const bf16_t* __restrict__ q,
+                                                          const bf16_t* __restrict__ k,
+                                                          float2* __restrict__ stats, Plan pl) {
+  using TL = Tile<HD>;
+  using ST = Stager<HD, NW>;
+  constexpr int KS = TL::kSteps;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * TL::kTileBytes];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int split = blockIdx.x, rb = blockIdx.y, bh = blockIdx.z;
   const int b = bh / pl.Hkv, h = bh % pl.Hkv;
-  const int row0 = rb * kRowsPerWG + wave * 64;
-  const bool active = row0 < pl.R;  // inactive waves only help staging the key tiles
+  const int row0 = rb * (32 * NQ * NW) + wave * (32 * NQ);
+  const bool active = row0 < pl.R;  // waves without rows only help staging the key tiles
+  const float c2 = pl.c2;
 
   const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
   const int t_begin = split * pl.tiles_per_split;
   const int t_end = min(tiles, t_begin + pl.tiles_per_split);
+  // a ragged last tile (N % 64 != 0) is handled after the pipelined loop over full tiles
+  const int t_full = (t_end == tiles && pl.N % kKeyTile != 0) ? t_end - 1 : t_end;
 
   // query fragments stay in registers for the whole key loop
-  bf16x8 qf[2][TL::kSteps];
+  bf16x8 qf[NQ][KS];
 #pragma unroll
-  for (int s = 0; s < 2; s++) {
+  for (int s = 0; s < NQ; s++) {
     const int r = row0 + s * 32 + l32;
-    const bool ok = active && r < pl.R;
+    const bool ok = r < pl.R;
     const int rr = ok ? r : 0;
     const bf16_t* qrow = q + b * pl.qsb + (int64_t)(h * pl.G + rr / pl.p) * pl.qsh +
-                         (int64_t)(rr % pl.p) * pl.qst;
+                         (int64_t)(rr % pl.p) * pl.qst + hi * 8;
 #pragma unroll
-    for (int j = 0; j < TL::kSteps; j++) {
+    for (int j = 0; j < KS; j++) {
       uint4 u = make_uint4(0, 0, 0, 0);
-      if (ok) u = *reinterpret_cast<const uint4*>(qrow + j * 16 + hi * 8);
+      if (ok) u = *reinterpret_cast<const uint4*>(qrow + j * 16);
       qf[s][j] = as_frag(u);
     }
   }
 
-  const bf16_t* kbase = k + b * pl.ksb + (int64_t)h * pl.ksh;
-  uint4 stage[TL::kLoads];
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < TL::kLoads; i++) {
-      const int c = tid + i * 256;
-      const int row = c / TL::kChunks, ch = c % TL::kChunks;
-      const int key = min(t * kKeyTile + row, pl.N - 1);  // tail rows are masked below
-      stage[i] = *reinterpret_cast<const uint4*>(kbase + (int64_t)key * pl.kst + ch * 8);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < TL::kLoads; i++) {
-      const int c = tid + i * 256;
-      const int row = c / TL::kChunks, ch = c % TL::kChunks;
-      *reinterpret_cast<uint4*>(lds + buf * TL::kTileBytes + row * TL::kRowBytes + ch * 16) = stage[i];
-    }
-  };
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(k + b * pl.ksb + (int64_t)h * pl.ksh);
+  const uint32_t kstride = (uint32_t)pl.kst * 2;
+  uint32_t koff[ST::kPer];
+  ST::offsets(koff, wave, lane, kstride);
 
-  float m[2] = {-INFINITY, -INFINITY};  // running max of the raw dot products
-  float D[2] = {0.f, 0.f};              // running sum of exp2((dot - m) * c2)
-  const float c2 = pl.c2;
+  RowStat st[NQ];
+#pragma unroll
+  for (int s = 0; s < NQ; s++) st[s].m = kNoMax, st[s].D = 0.f;
+  f32x16 accA, accB;
+#pragma unroll
+  for (int v = 0; v < 16; v++) accA[v] = accB[v] = kMasked;  // the tile "before the first": a no-op
 
-  if (t_begin < t_end) load_tile(t_begin);
+  const uint32_t lds0 = lds_address(lds);
+  if (t_begin < t_full) ST::run(lds0, kbase + (size_t)t_begin * kKeyTile * kstride, koff, wave);
+  wait_vmem();
+  __syncthreads();
   int buf = 0;
-  for (int t = t_begin; t < t_end; t++) {
-    store_tile(buf);
+  // Units of one tile, in order: (ks, s) for key half ks in {0,1}, query sub-tile s in 0..NQ-1.
+  // Unit u accumulates into accA (u even) or accB (u odd) while unit u-1 is folded into the
+  // statistics of its query sub-tile.  2*NQ is even, so the parity carries over between tiles.
+  for (int t = t_begin; t < t_full; t++) {
+    const unsigned char* cur = lds + buf * TL::kTileBytes;
+    if (t + 1 < t_full && !(pl.debug & 2))
+      ST::run(lds0 + (buf ^ 1) * TL::kTileBytes, kbase + (size_t)(t + 1) * kKeyTile * kstride, koff, wave);
+    if (active && !(pl.debug & 1)) {
+      bf16x8 kf[KS];  // one 32-key half at a time, refilled once its last MFMA has been issued
+      if (pl.debug & 4) { for (int j = 0; j < KS; j++) kf[j] = qf[0][j]; } else
+      read_frags<HD>(kf, cur, 0, l32, hi);
+#pragma unroll
+      for (int u = 0; u < 2 * NQ; u++) {
+        const int s = u % NQ, sp = (u + NQ * 2 - 1) % NQ;
+        if (u == NQ && !(pl.debug & 4)) read_frags<HD>(kf, cur, 1, l32, hi);
+        if (u & 1) stats_unit<KS>(accB, kf, qf[s], accA, st[sp], c2);
+        else       stats_unit<KS>(accA, kf, qf[s], accB, st[sp], c2);
+      }
+    }
+    wait_vmem();
+    if (!(pl.debug & 8)) __syncthreads();
+    buf ^= 1;
+  }
+  if (active) stats_fold(accB, st[NQ - 1], c2);  // last unit in flight (or the filler)
+
+  if (t_full < t_end) {
+    // ragged last tile: rows beyond N re-read the last key and are masked out of the statistics
+    const int t = t_full;
+    const int nrows = pl.N - t * kKeyTile;  // 1..63
+    const unsigned char* tile = kbase + (size_t)t * kKeyTile * kstride;
+    __syncthreads();  // every wave is done reading both buffers
+    ST::run_rows(lds0, wave, lane, [=](int row) { return tile + (size_t)min(row, nrows - 1) * kstride; });
+    wait_vmem();
     __syncthreads();
-    if (t + 1 < t_end) load_tile(t + 1);
     if (active) {
-      const bool tail = (t + 1) * kKeyTile > pl.N;
-#pragma unroll
       for (int ks = 0; ks < 2; ks++) {
-        bf16x8 kf[TL::kSteps];
-        const unsigned char* src = lds + buf * TL::kTileBytes + (ks * 32 + l32) * TL::kRowBytes + hi * 16;
+        bf16x8 kf[KS];
+        read_frags<HD>(kf, lds, ks, l32, hi);
 #pragma unroll
-        for (int j = 0; j < TL::kSteps; j++)
-          kf[j] = as_frag(*reinterpret_cast<const uint4*>(src + j * 32));
+        for (int s = 0; s < NQ; s++) {
+          f32x16 acc;
+          mfma_chain<KS>(acc, kf, qf[s]);
 #pragma unroll
-        for (int s = 0; s < 2; s++) {
-          f32x16 acc = {0};
-#pragma unroll
-          for (int j = 0; j < TL::kSteps; j++)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[s][j], acc, 0, 0, 0);
-          if (tail) {
-            const int kb = t * kKeyTile + ks * 32 + hi * 4;
-#pragma unroll
-            for (int v = 0; v < 16; v++)
-              if (kb + (v >> 2) * 8 + (v & 3) >= pl.N) acc[v] = -INFINITY;
-          }
-          float tmax = acc[0];
-#pragma unroll
-          for (int v = 1; v < 16; v++) tmax = fmaxf(tmax, acc[v]);
-          const float mn = fmaxf(m[s], tmax);
-          const float mref = mn == -INFINITY ? 0.f : mn;  // all 16 keys masked and nothing seen yet
-          const float mc = mref * c2;
-          float sum = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; v++) sum += fast_exp2(fmaf(acc[v], c2, -mc));
-          D[s] = D[s] * fast_exp2(fmaf(m[s], c2, -mc)) + sum;
-          m[s] = mn;
+          for (int v = 0; v < 16; v++)
+            if (ks * 32 + (v >> 2) * 8 + hi * 4 + (v & 3) >= nrows) acc[v] = kMasked;
+          stats_fold(acc, st[s], c2);
         }
       }
     }
-    buf ^= 1;
   }
 
   if (!active) return;
 #pragma unroll
-  for (int s = 0; s < 2; s++) {
+  for (int s = 0; s < NQ; s++) {
     // lanes l and l^32 hold the same query row over disjoint keys
-    const float mo = __shfl_xor(m[s], 32), Do = __shfl_xor(D[s], 32);
-    const float mn = fmaxf(m[s], mo);
-    const float mref = mn == -INFINITY ? 0.f : mn;
-    const float Dn = D[s] * fast_exp2((m[s] - mref) * c2) + Do * fast_exp2((mo - mref) * c2);
+    const float mo = __shfl_xor(st[s].m, 32), Do = __shfl_xor(st[s].D, 32);
+    const float mn = fmaxf(st[s].m, mo);
+    const float Dn = st[s].D * ex2((st[s].m - mn) * c2) + Do * ex2((mo - mn) * c2);
     const int r = row0 + s * 32 + l32;
     if (hi == 0 && r < pl.R)
       stats[((size_t)bh * pl.n_splits + split) * pl.Rpad + r] = make_float2(mn * c2, Dn);
@@ -157,32 +342,108 @@ __global__ __launch_bounds__(256, 2) void score_stats(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------ pass 2
+// Column reduction of the previous accumulator tile (16 query rows of one key),
+// sliced like the statistics above.  nl[v] = -(base-2 lse) of the value's row.
+template <int REDUCE>
+__device__ __forceinline__ float col_group(const f32x16& P, const float (&nl)[16], int g, float c2) {
+  const float x0 = fmaf(P[4 * g + 0], c2, nl[4 * g + 0]), x1 = fmaf(P[4 * g + 1], c2, nl[4 * g + 1]);
+  const float x2 = fmaf(P[4 * g + 2], c2, nl[4 * g + 2]), x3 = fmaf(P[4 * g + 3], c2, nl[4 * g + 3]);
+  if (REDUCE == EPICACHE_REDUCE_MAX) return fmaxf(max3(x0, x1, x2), x3);
+  return (ex2(x0) + ex2(x1)) + (ex2(x2) + ex2(x3));
+}
+
+template <int REDUCE>
+__device__ __forceinline__ float col_merge(float col, float a, float b, float c, float d) {
+  if (REDUCE == EPICACHE_REDUCE_MAX) return max3(max3(a, b, c), d, col);
+  return col + ((a + b) + (c + d));
+}
+
+template <int KS, int REDUCE>
+__device__ __forceinline__ void reduce_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
+                                            const f32x16& P, const float (&nl)[16], float& col, float c2) {
+  float s0, s1, s2, s3;
+  const f32x16 zero = {0};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
+  s0 = col_group<REDUCE>(P, nl, 0, c2);
+  pin(s0);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
+  s1 = col_group<REDUCE>(P, nl, 1, c2);
+  pin(s1);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], acc, 0, 0, 0);
+  s2 = col_group<REDUCE>(P, nl, 2, c2);
+  pin(s2);
+  fence_sched();
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], acc, 0, 0, 0);
+  s3 = col_group<REDUCE>(P, nl, 3, c2);
+  col = col_merge<REDUCE>(col, s0, s1, s2, s3);
+  pin(col);
+  fence_sched();
+#pragma unroll
+  for (int j = 4; j < KS; j++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc, 0, 0, 0);
+  fence_sched();
+}
+
+__device__ __forceinline__ void read_nlse(float (&nl)[16], const float* nlse, int row0, int hi) {
+#pragma unroll
+  for (int g4 = 0; g4 < 4; g4++) {
+    const float4 x = *reinterpret_cast<const float4*>(nlse + row0 + g4 * 8 + hi * 4);
+    nl[g4 * 4 + 0] = x.x, nl[g4 * 4 + 1] = x.y, nl[g4 * 4 + 2] = x.z, nl[g4 * 4 + 3] = x.w;
+  }
+}
+
 template <int HD, int REDUCE>
 __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict__ q,
                                                        const bf16_t* __restrict__ k,
                                                        const float2* __restrict__ stats,
                                                        float* __restrict__ scores, Plan pl) {
   using TL = Tile<HD>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int KS = TL::kSteps;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* lds = smem;                                            // 2 query tiles
-  float* nlse = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);    // [Rpad] minus base-2 lse
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  float* nlse = reinterpret_cast<float*>(smem + 2 * TL::kTileBytes);    // [Rpad + 64] minus base-2 lse
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int bh = blockIdx.y, b = bh / pl.Hkv, h = bh % pl.Hkv;
   const int key0 = blockIdx.x * kKeysPerWG + wave * 64;
   const float c2 = pl.c2;
 
+  using ST = Stager<HD, 4>;
+  const unsigned char* qbase = reinterpret_cast<const unsigned char*>(q + b * pl.qsb + (int64_t)(h * pl.G) * pl.qsh);
+  const size_t qsh = (size_t)pl.qsh * 2;
+  const uint32_t qstride = (uint32_t)pl.qst * 2;
+  const int p = pl.p, last_row = pl.R - 1;
+  const bool dense_tiles = p % 64 == 0;  // every 64-row tile lies inside one query head
+  uint32_t qoff[ST::kPer];
+  ST::offsets(qoff, wave, lane, qstride);
+  const uint32_t lds0 = lds_address(lds);
+  auto stage_queries = [&](uint32_t dst, int t) {
+    if (dense_tiles) {
+      const int r0 = t * 64;
+      ST::run(dst, qbase + (size_t)(r0 / p) * qsh + (size_t)(r0 % p) * qstride, qoff, wave);
+    } else {
+      // rows beyond R re-read the last row; their -lse is -inf, so they contribute nothing
+      ST::run_rows(dst, wave, lane, [=](int row) {
+        const int r = min(t * 64 + row, last_row);
+        return qbase + (size_t)(r / p) * qsh + (size_t)(r % p) * qstride;
+      });
+    }
+  };
+  stage_queries(lds0, 0);
+
   // combine the key splits of pass 1 into one log-sum-exp per query row
-  for (int r = tid; r < pl.Rpad; r += 256) {
-    float val = -INFINITY;  // padding rows: weight exp2(-inf) = 0
+  for (int r = tid; r < pl.Rpad + 64; r += 256) {
+    float val = -INFINITY;
     if (r < pl.R) {
       const float2* st = stats + (size_t)bh * pl.n_splits * pl.Rpad + r;
-      float mx = -INFINITY;
-      for (int s = 0; s < pl.n_splits; s++) mx = fmaxf(mx, st[(size_t)s * pl.Rpad].x);
+      float mx = st[0].x;
+      for (int s = 1; s < pl.n_splits; s++) mx = fmaxf(mx, st[(size_t)s * pl.Rpad].x);
       float den = 0.f;
       for (int s = 0; s < pl.n_splits; s++) {
         const float2 e = st[(size_t)s * pl.Rpad];
-        den += e.y * fast_exp2(e.x - mx);
+        den += e.y * ex2(e.x - mx);
       }
       val = -(mx + __log2f(den));
     }
@@ -191,85 +452,57 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
 
   // key fragments of this wave stay in registers for the whole query loop
   const bf16_t* kbase = k + b * pl.ksb + (int64_t)h * pl.ksh;
-  bf16x8 kf[2][TL::kSteps];
+  bf16x8 kf[2][KS];
 #pragma unroll
   for (int s = 0; s < 2; s++) {
     const int key = min(key0 + s * 32 + l32, pl.N - 1);
     const bf16_t* krow = kbase + (int64_t)key * pl.kst + hi * 8;
 #pragma unroll
-    for (int j = 0; j < TL::kSteps; j++)
+    for (int j = 0; j < KS; j++)
       kf[s][j] = as_frag(*reinterpret_cast<const uint4*>(krow + j * 16));
   }
-
-  const bf16_t* qbase = q + b * pl.qsb + (int64_t)(h * pl.G) * pl.qsh;
-  uint4 stage[TL::kLoads];
-  auto load_tile = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < TL::kLoads; i++) {
-      const int c = tid + i * 256;
-      const int row = c / TL::kChunks, ch = c % TL::kChunks;
-      const int r = t * 64 + row;
-      uint4 u = make_uint4(0, 0, 0, 0);
-      if (r < pl.R)
-        u = *reinterpret_cast<const uint4*>(qbase + (int64_t)(r / pl.p) * pl.qsh +
-                                            (int64_t)(r % pl.p) * pl.qst + ch * 8);
-      stage[i] = u;
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < TL::kLoads; i++) {
-      const int c = tid + i * 256;
-      const int row = c / TL::kChunks, ch = c % TL::kChunks;
-      *reinterpret_cast<uint4*>(lds + buf * TL::kTileBytes + row * TL::kRowBytes + ch * 16) = stage[i];
-    }
-  };
 
   // SUM: running sum of weights.  MAX: running max of the base-2 log weight
   // (exp2 is monotone, so one exponential per key at the end is enough).
   float col[2];
   col[0] = col[1] = REDUCE == EPICACHE_REDUCE_MAX ? -INFINITY : 0.f;
+  f32x16 accA, accB;
+#pragma unroll
+  for (int v = 0; v < 16; v++) accA[v] = accB[v] = 0.f;
+  // "previous tile" of the very first unit: rows [Rpad, Rpad+64) of nlse are -inf, i.e. a no-op
+  float nlP[16], nlC[16];
+
+  wait_vmem();
+  __syncthreads();  // query tile 0 and nlse[] are in LDS
+  read_nlse(nlP, nlse, pl.Rpad, hi);
 
   const int qtiles = pl.Rpad / 64;
-  load_tile(0);
   int buf = 0;
+  // Units of one query tile: (qs, s) for qs in {0,1} (32-row halves), s in {0,1} (key halves of the
+  // wave): u = 2*qs + s accumulates into accA (u even) / accB (u odd) while unit u-1 is reduced.
   for (int t = 0; t < qtiles; t++) {
-    store_tile(buf);
-    __syncthreads();  // also orders the nlse[] writes above before their first use
-    if (t + 1 < qtiles) load_tile(t + 1);
-#pragma unroll
-    for (int qs = 0; qs < 2; qs++) {
-      bf16x8 qf[TL::kSteps];
-      const unsigned char* src = lds + buf * TL::kTileBytes + (qs * 32 + l32) * TL::kRowBytes + hi * 16;
-#pragma unroll
-      for (int j = 0; j < TL::kSteps; j++)
-        qf[j] = as_frag(*reinterpret_cast<const uint4*>(src + j * 32));
-      float nl[16];
-#pragma unroll
-      for (int g4 = 0; g4 < 4; g4++) {
-        const float4 x = *reinterpret_cast<const float4*>(nlse + t * 64 + qs * 32 + g4 * 8 + hi * 4);
-        nl[g4 * 4 + 0] = x.x, nl[g4 * 4 + 1] = x.y, nl[g4 * 4 + 2] = x.z, nl[g4 * 4 + 3] = x.w;
-      }
-#pragma unroll
-      for (int s = 0; s < 2; s++) {
-        f32x16 acc = {0};
-#pragma unroll
-        for (int j = 0; j < TL::kSteps; j++)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[j], kf[s][j], acc, 0, 0, 0);
-        if (REDUCE == EPICACHE_REDUCE_MAX) {
-          float x = col[s];
-#pragma unroll
-          for (int v = 0; v < 16; v++) x = fmaxf(x, fmaf(acc[v], c2, nl[v]));
-          col[s] = x;
-        } else {
-          float x = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; v++) x += fast_exp2(fmaf(acc[v], c2, nl[v]));
-          col[s] += x;
-        }
-      }
+    const unsigned char* cur = lds + buf * TL::kTileBytes;
+    if (t + 1 < qtiles && !(pl.debug & 2)) stage_queries(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
+    if (!(pl.debug & 1)) {
+    bf16x8 qf0[KS], qf1[KS];
+    read_frags<HD>(qf0, cur, 0, l32, hi);
+    read_frags<HD>(qf1, cur, 1, l32, hi);
+    read_nlse(nlC, nlse, t * 64, hi);
+    // unit 0: rows qs=0, keys s=0; previous unit = (prev tile, qs=1, s=1) with nlP
+    reduce_unit<KS, REDUCE>(accA, qf0, kf[0], accB, nlP, col[1], c2);
+    read_nlse(nlP, nlse, t * 64 + 32, hi);
+    reduce_unit<KS, REDUCE>(accB, qf0, kf[1], accA, nlC, col[0], c2);
+    reduce_unit<KS, REDUCE>(accA, qf1, kf[0], accB, nlC, col[1], c2);
+    reduce_unit<KS, REDUCE>(accB, qf1, kf[1], accA, nlP, col[0], c2);
     }
+    wait_vmem();
+    __syncthreads();
     buf ^= 1;
+  }
+  {  // drain: last unit (qs=1, s=1) sits in accB with nlP
+    const float s0 = col_group<REDUCE>(accB, nlP, 0, c2), s1 = col_group<REDUCE>(accB, nlP, 1, c2);
+    const float s2 = col_group<REDUCE>(accB, nlP, 2, c2), s3 = col_group<REDUCE>(accB, nlP, 3, c2);
+    col[1] = col_merge<REDUCE>(col[1], s0, s1, s2, s3);
   }
 
 #pragma unroll
@@ -277,11 +510,18 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
     // lanes l and l^32 hold the same key over disjoint query rows
     const float o = __shfl_xor(col[s], 32);
     float val;
-    if (REDUCE == EPICACHE_REDUCE_MAX) val = fast_exp2(fmaxf(col[s], o));
+    if (REDUCE == EPICACHE_REDUCE_MAX) val = ex2(fmaxf(col[s], o));
     else val = col[s] + o;
     const int key = key0 + s * 32 + l32;
     if (hi == 0 && key < pl.N) scores[(size_t)bh * pl.N + key] = val;
   }
+}
+
+template <int HD, int NQ, int NW>
+void launch_stats(const Plan& pl, const bf16_t* q, const bf16_t* k, float2* stats, hipStream_t stream) {
+  const int rows_per_wg = 32 * NQ * NW;
+  dim3 grid(pl.n_splits, (pl.R + rows_per_wg - 1) / rows_per_wg, pl.nb * pl.Hkv);
+  hipLaunchKernelGGL((score_stats<HD, NQ, NW>), grid, dim3(NW * 64), 0, stream, q, k, stats, pl);
 }
 
 template <int HD>
@@ -289,10 +529,15 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
                      float2* stats, hipStream_t stream) {
   using TL = Tile<HD>;
   const int nbh = pl.nb * pl.Hkv;
-  dim3 g1(pl.n_splits, (pl.R + kRowsPerWG - 1) / kRowsPerWG, nbh);
-  hipLaunchKernelGGL(score_stats<HD>, g1, dim3(256), 0, stream, q, k, stats, pl);
+  switch (pl.stats_rows_per_wg) {
+    case 256: launch_stats<HD, 2, 4>(pl, q, k, stats, stream); break;
+    case 192: launch_stats<HD, 2, 3>(pl, q, k, stats, stream); break;
+    case 128: launch_stats<HD, 1, 4>(pl, q, k, stats, stream); break;
+    case 64: launch_stats<HD, 1, 2>(pl, q, k, stats, stream); break;
+    default: launch_stats<HD, 1, 1>(pl, q, k, stats, stream); break;
+  }
   dim3 g2((pl.N + kKeysPerWG - 1) / kKeysPerWG, nbh);
-  const size_t smem = 2 * TL::kTileBytes + (size_t)pl.Rpad * sizeof(float);
+  const size_t smem = 2 * TL::kTileBytes + (size_t)(pl.Rpad + 64) * sizeof(float);
   if (pl.reduce == EPICACHE_REDUCE_MAX)
     hipLaunchKernelGGL((score_reduce<HD, EPICACHE_REDUCE_MAX>), g2, dim3(256), smem, stream, q, k,
                        stats, scores, pl);
