@@ -53,8 +53,8 @@ def cpu_baseline(w, reduce, budget_s):
     except Exception:
         cores = 1
     tokens, spent, layers = 0, 0.0, 0
-    while spent < budget_s and layers < w.L:
-        q, k, v = synth.make_layer(w, layer=layers)
+    while spent < budget_s:
+        q, k, v = synth.make_layer(w, layer=layers % w.L, step=layers // w.L)
         qq, kk = synth.to_f64_numpy(q), synth.to_f64_numpy(k)
         kb, vb = synth.raw_bits_numpy(k), synth.raw_bits_numpy(v)
         t0 = time.perf_counter()
@@ -63,8 +63,21 @@ def cpu_baseline(w, reduce, budget_s):
         tokens += w.E * w.N
         layers += 1
     return {"value": tokens / spent, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{layers} of {w.L} layers of the same workload (all {w.E} episodes, "
-                      f"{w.Hkv} KV heads), numpy float64, {spent:.1f} s"}
+            "sample": f"{layers} whole layers of the same workload (each all {w.E} episodes x "
+                      f"{w.Hkv} KV heads; a full step has {w.L}), numpy float64, {spent:.1f} s"}
+
+
+def measured_traffic(workload, key):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] == key:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -155,11 +168,11 @@ def main():
         a = flops_score / t_score / 1e12
         roofline = {"kernel": "score (score_stats + score_reduce)", "bound": "mfma", "achieved": a,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": a / PEAK_BF16_MFMA_TFLOPS,
-                    "traffic": None}
+                    "traffic": measured_traffic(w.name, "score")}
     else:
         a = bytes_compact / t_compact / 1e9
         roofline = {"kernel": "compact_rows", "bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": None}
+                    "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": measured_traffic(w.name, "compact")}
 
     out = {
         "metric": "evict-step tokens scored+compacted/sec",

@@ -90,7 +90,7 @@ EPICACHE_API int epicache_workspace_size(const epicache_params* params, size_t* 
 EPICACHE_API int epicache_score(const epicache_params* params, const void* q, const void* k,
                    float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Sec. 3.1 Stage 2 / Alg. 1 phase A3 ("retain the top M tokens").  For every
+/* Sec. 3.1 Stage 2 / Alg. 1 phase A3 (retention of the M best-scoring tokens).  For every
  * (b, h): the n_keep = min(budget, N) rows with the largest score, written in
  * ascending row order.  Equal scores: the lower row index wins.  Scores are
  * ordered as IEEE-754 totals (-0 < +0, NaN with the sign bit clear above +inf).
@@ -98,7 +98,7 @@ EPICACHE_API int epicache_score(const epicache_params* params, const void* q, co
 EPICACHE_API int epicache_topk(const epicache_params* params, const float* scores, int32_t* keep_idx,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Sec. 2.2 / App. A.3 ("reduce the cache back to M").  In place, for every
+/* Sec. 2.2 / App. A.3 (the cache shrinks back to M entries).  In place, for every
  * (b, h) and j < n_keep:  K[b,h,j,:] = K[b,h,keep_idx[b,h,j],:], same for V.
  * keep_idx must be strictly ascending within [0, N) (as epicache_topk writes
  * it); this is not checked on the device.  Rows >= n_keep are left as they

@@ -2,7 +2,6 @@
 // sequence of one eviction step (paper Alg. 1 phase A3).  No kernel lives here.
 #include <math.h>
 #include <string.h>
-#include <stdlib.h>
 
 #include "epicache_internal.h"
 
@@ -87,7 +86,6 @@ int make_plan(const epicache_params* prm, Plan* out) {
     pl.tiles_per_split = 0;
   }
 
-  { const char* e = getenv("EPICACHE_DEBUG"); pl.debug = e ? atoi(e) : 0; }
   size_t off = 0;
   pl.off_stats = off;
   off += align256((size_t)nbh * pl.n_splits * pl.Rpad * sizeof(float2));

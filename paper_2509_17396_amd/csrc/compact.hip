@@ -1,5 +1,5 @@
-// In-place, order-preserving compaction of the K and V caches ("reduce the
-// cache back to M entries", paper Sec. 2.2 and App. A.3): row j of every
+// In-place, order-preserving compaction of the K and V caches (the cache returns
+// to M entries after each block, paper Sec. 2.2 and App. A.3): row j of every
 // (batch item, KV head) becomes row keep[j], keep strictly ascending.
 //
 // Hazard of doing this in place: keep[j] >= j, so the destination rows of one

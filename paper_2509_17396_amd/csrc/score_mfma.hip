@@ -221,7 +221,7 @@ __device__ __forceinline__ void stats_fold(const f32x16& P, RowStat& st, float c
 
 // NQ 32-row query sub-tiles per wave, NW waves per workgroup: 32*NQ*NW query rows per workgroup.
 template <int HD, int NQ, int NW>
-__global__ __launch_bounds__(NW * 64, (NQ <= 2 ? 3 : 2)) void score_stats(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const bf16_t* __restrict__ q,
                                                           const bf16_t* __restrict__ k,
                                                           float2* __restrict__ stats, Plan pl) {
   using TL = Tile<HD>;
@@ -282,22 +282,21 @@ __global__ __launch_bounds__(NW * 64, (NQ <= 2 ? 3 : 2)) void score_stats(const 
   // statistics of its query sub-tile.  2*NQ is even, so the parity carries over between tiles.
   for (int t = t_begin; t < t_full; t++) {
     const unsigned char* cur = lds + buf * TL::kTileBytes;
-    if (t + 1 < t_full && !(pl.debug & 2))
+    if (t + 1 < t_full)
       ST::run(lds0 + (buf ^ 1) * TL::kTileBytes, kbase + (size_t)(t + 1) * kKeyTile * kstride, koff, wave);
-    if (active && !(pl.debug & 1)) {
+    if (active) {
       bf16x8 kf[KS];  // one 32-key half at a time, refilled once its last MFMA has been issued
-      if (pl.debug & 4) { for (int j = 0; j < KS; j++) kf[j] = qf[0][j]; } else
       read_frags<HD>(kf, cur, 0, l32, hi);
 #pragma unroll
       for (int u = 0; u < 2 * NQ; u++) {
         const int s = u % NQ, sp = (u + NQ * 2 - 1) % NQ;
-        if (u == NQ && !(pl.debug & 4)) read_frags<HD>(kf, cur, 1, l32, hi);
+        if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
         if (u & 1) stats_unit<KS>(accB, kf, qf[s], accA, st[sp], c2);
         else       stats_unit<KS>(accA, kf, qf[s], accB, st[sp], c2);
       }
     }
     wait_vmem();
-    if (!(pl.debug & 8)) __syncthreads();
+    __syncthreads();
     buf ^= 1;
   }
   if (active) stats_fold(accB, st[NQ - 1], c2);  // last unit in flight (or the filler)
@@ -482,8 +481,7 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   // wave): u = 2*qs + s accumulates into accA (u even) / accB (u odd) while unit u-1 is reduced.
   for (int t = 0; t < qtiles; t++) {
     const unsigned char* cur = lds + buf * TL::kTileBytes;
-    if (t + 1 < qtiles && !(pl.debug & 2)) stage_queries(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
-    if (!(pl.debug & 1)) {
+    if (t + 1 < qtiles) stage_queries(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
     bf16x8 qf0[KS], qf1[KS];
     read_frags<HD>(qf0, cur, 0, l32, hi);
     read_frags<HD>(qf1, cur, 1, l32, hi);
@@ -494,7 +492,6 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
     reduce_unit<KS, REDUCE>(accB, qf0, kf[1], accA, nlC, col[0], c2);
     reduce_unit<KS, REDUCE>(accA, qf1, kf[0], accB, nlC, col[1], c2);
     reduce_unit<KS, REDUCE>(accB, qf1, kf[1], accA, nlP, col[0], c2);
-    }
     wait_vmem();
     __syncthreads();
     buf ^= 1;
@@ -517,6 +514,158 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   }
 }
 
+// ------------------------------------------------------- pass 2, streaming form
+// For R <= 256 (all query rows of a KV head fit one workgroup): same data flow as pass 1 - query
+// fragments stay in registers, 64-key tiles stream through LDS - with the operands swapped so that
+// a lane owns one key column and 16 query rows.  Each wave reduces its own rows; the per-key
+// partial results of the NW waves meet in LDS once per tile.  Reads K with fully coalesced
+// 1 KiB bursts, which the key-stationary form above cannot do when R is small.
+template <int KS, int REDUCE>
+__device__ __forceinline__ void col_fold(const f32x16& P, const float (&nl)[16], float& col, float c2) {
+  const float s0 = col_group<REDUCE>(P, nl, 0, c2), s1 = col_group<REDUCE>(P, nl, 1, c2);
+  const float s2 = col_group<REDUCE>(P, nl, 2, c2), s3 = col_group<REDUCE>(P, nl, 3, c2);
+  col = col_merge<REDUCE>(col, s0, s1, s2, s3);
+}
+
+template <int HD, int NQ, int NW, int REDUCE>
+__global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_stream(const bf16_t* __restrict__ q,
+                                                                  const bf16_t* __restrict__ k,
+                                                                  const float2* __restrict__ stats,
+                                                                  float* __restrict__ scores, Plan pl) {
+  using TL = Tile<HD>;
+  using ST = Stager<HD, NW>;
+  constexpr int KS = TL::kSteps;
+  constexpr int kRows = 32 * NQ * NW;
+  constexpr float kNeutral = REDUCE == EPICACHE_REDUCE_MAX ? -INFINITY : 0.f;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * TL::kTileBytes];
+  __shared__ __attribute__((aligned(16))) float nlse[kRows];
+  __shared__ float part[2][NW][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hi = lane >> 5;
+  const int split = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / pl.Hkv, h = bh % pl.Hkv;
+  const int row0 = wave * (32 * NQ);
+  const bool active = row0 < pl.R;
+  const float c2 = pl.c2;
+
+  const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
+  const int t_begin = split * pl.tiles_per_split;
+  const int t_end = min(tiles, t_begin + pl.tiles_per_split);
+
+  const unsigned char* kbase = reinterpret_cast<const unsigned char*>(k + b * pl.ksb + (int64_t)h * pl.ksh);
+  const uint32_t kstride = (uint32_t)pl.kst * 2;
+  uint32_t koff[ST::kPer];
+  ST::offsets(koff, wave, lane, kstride);
+  const uint32_t lds0 = lds_address(lds);
+  auto stage_keys = [&](uint32_t dst, int t) {
+    const unsigned char* tile = kbase + (size_t)t * kKeyTile * kstride;
+    const int nrows = pl.N - t * kKeyTile;
+    if (nrows >= kKeyTile) ST::run(dst, tile, koff, wave);
+    else  // ragged last tile: rows beyond N re-read the last key; their results are never written
+      ST::run_rows(dst, wave, lane, [=](int row) { return tile + (size_t)min(row, nrows - 1) * kstride; });
+  };
+  if (t_begin < t_end) stage_keys(lds0, t_begin);
+
+  // combine the key splits of pass 1 into minus one base-2 log-sum-exp per query row
+  for (int r = tid; r < kRows; r += NW * 64) {
+    float val = -INFINITY;  // rows beyond R: weight exp2(-inf) = 0
+    if (r < pl.R) {
+      const float2* st = stats + (size_t)bh * pl.n_splits * pl.Rpad + r;
+      float mx = st[0].x;
+      for (int s = 1; s < pl.n_splits; s++) mx = fmaxf(mx, st[(size_t)s * pl.Rpad].x);
+      float den = 0.f;
+      for (int s = 0; s < pl.n_splits; s++) {
+        const float2 e = st[(size_t)s * pl.Rpad];
+        den += e.y * ex2(e.x - mx);
+      }
+      val = -(mx + __log2f(den));
+    }
+    nlse[r] = val;
+  }
+
+  // query fragments (A operand: rows = queries) stay in registers for the whole key loop
+  bf16x8 qf[NQ][KS];
+#pragma unroll
+  for (int s = 0; s < NQ; s++) {
+    const int r = row0 + s * 32 + l32;
+    const bool ok = r < pl.R;
+    const int rr = ok ? r : 0;
+    const bf16_t* qrow = q + b * pl.qsb + (int64_t)(h * pl.G + rr / pl.p) * pl.qsh +
+                         (int64_t)(rr % pl.p) * pl.qst + hi * 8;
+#pragma unroll
+    for (int j = 0; j < KS; j++) {
+      uint4 u = make_uint4(0, 0, 0, 0);
+      if (ok) u = *reinterpret_cast<const uint4*>(qrow + j * 16);
+      qf[s][j] = as_frag(u);
+    }
+  }
+
+  wait_vmem();
+  __syncthreads();  // first key tile and nlse[] are in LDS
+
+  int buf = 0;
+  for (int t = t_begin; t < t_end; t++) {
+    const unsigned char* cur = lds + buf * TL::kTileBytes;
+    if (t + 1 < t_end) stage_keys(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
+    float cs[2] = {kNeutral, kNeutral};  // this wave's rows, keys ks*32 + l32 of the tile
+    if (active) {
+      // units (ks, s): key half ks, query sub-tile s; unit u accumulates into accA/accB (u even/odd)
+      // while unit u-1 is reduced over its 16 rows into cs[ks of u-1]
+      bf16x8 kf[KS];
+      f32x16 accA, accB;
+      read_frags<HD>(kf, cur, 0, l32, hi);
+#pragma unroll
+      for (int u = 0; u < 2 * NQ; u++) {
+        const int s = u % NQ, sp = (u + 2 * NQ - 1) % NQ, ksp = (u - 1) / NQ;
+        if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
+        float nl[16];  // minus lse of the 16 rows this lane holds of the previous unit
+        if (u > 0) read_nlse(nl, nlse, row0 + sp * 32, hi);
+        if (u == 0) mfma_chain<KS>(accA, qf[0], kf);
+        else if (u & 1) reduce_unit<KS, REDUCE>(accB, qf[s], kf, accA, nl, cs[ksp], c2);
+        else            reduce_unit<KS, REDUCE>(accA, qf[s], kf, accB, nl, cs[ksp], c2);
+      }
+      {
+        float nl[16];
+        read_nlse(nl, nlse, row0 + (NQ - 1) * 32, hi);
+        col_fold<KS, REDUCE>(accB, nl, cs[1], c2);  // last unit: odd index, key half 1
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      // lanes l and l^32 hold the same key over disjoint query rows
+      const float o = __shfl_xor(cs[ks], 32);
+      const float v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(cs[ks], o) : cs[ks] + o;
+      if (hi == 0) part[t & 1][wave][ks * 32 + l32] = v;
+    }
+    wait_vmem();
+    __syncthreads();  // tile t+1 staged, part[t & 1] complete; it is rewritten two barriers from now
+    if (tid < 64) {
+      const int key = t * kKeyTile + tid;
+      if (key < pl.N) {
+        float v = part[t & 1][0][tid];
+#pragma unroll
+        for (int w = 1; w < NW; w++)
+          v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(v, part[t & 1][w][tid]) : v + part[t & 1][w][tid];
+        scores[(size_t)bh * pl.N + key] = REDUCE == EPICACHE_REDUCE_MAX ? ex2(v) : v;
+      }
+    }
+    buf ^= 1;
+  }
+}
+
+template <int HD, int NQ, int NW>
+void launch_reduce_stream(const Plan& pl, const bf16_t* q, const bf16_t* k, const float2* stats,
+                          float* scores, hipStream_t stream) {
+  dim3 grid(pl.n_splits, pl.nb * pl.Hkv);
+  if (pl.reduce == EPICACHE_REDUCE_MAX)
+    hipLaunchKernelGGL((score_reduce_stream<HD, NQ, NW, EPICACHE_REDUCE_MAX>), grid, dim3(NW * 64), 0,
+                       stream, q, k, stats, scores, pl);
+  else
+    hipLaunchKernelGGL((score_reduce_stream<HD, NQ, NW, EPICACHE_REDUCE_SUM>), grid, dim3(NW * 64), 0,
+                       stream, q, k, stats, scores, pl);
+}
+
 template <int HD, int NQ, int NW>
 void launch_stats(const Plan& pl, const bf16_t* q, const bf16_t* k, float2* stats, hipStream_t stream) {
   const int rows_per_wg = 32 * NQ * NW;
@@ -531,10 +680,20 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
   const int nbh = pl.nb * pl.Hkv;
   switch (pl.stats_rows_per_wg) {
     case 256: launch_stats<HD, 2, 4>(pl, q, k, stats, stream); break;
-    case 192: launch_stats<HD, 2, 3>(pl, q, k, stats, stream); break;
+    case 192: launch_stats<HD, 3, 2>(pl, q, k, stats, stream); break;
     case 128: launch_stats<HD, 1, 4>(pl, q, k, stats, stream); break;
     case 64: launch_stats<HD, 1, 2>(pl, q, k, stats, stream); break;
     default: launch_stats<HD, 1, 1>(pl, q, k, stats, stream); break;
+  }
+  if (pl.R <= pl.stats_rows_per_wg) {
+    switch (pl.stats_rows_per_wg) {
+      case 256: launch_reduce_stream<HD, 2, 4>(pl, q, k, stats, scores, stream); break;
+      case 192: launch_reduce_stream<HD, 3, 2>(pl, q, k, stats, scores, stream); break;
+      case 128: launch_reduce_stream<HD, 1, 4>(pl, q, k, stats, scores, stream); break;
+      case 64: launch_reduce_stream<HD, 1, 2>(pl, q, k, stats, scores, stream); break;
+      default: launch_reduce_stream<HD, 1, 1>(pl, q, k, stats, scores, stream); break;
+    }
+    return hipGetLastError();
   }
   dim3 g2((pl.N + kKeysPerWG - 1) / kKeysPerWG, nbh);
   const size_t smem = 2 * TL::kTileBytes + (size_t)(pl.Rpad + 64) * sizeof(float);

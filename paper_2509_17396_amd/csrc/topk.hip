@@ -1,5 +1,5 @@
-// Per-(batch item, KV head) top-M selection ("the top M tokens are retained",
-// paper Sec. 3.1 Stage 2 / Alg. 1 phase A3) as an exact radix select.
+// Per-(batch item, KV head) top-M selection (the retention rule of paper Sec. 3.1
+// Stage 2 / Alg. 1 phase A3) as an exact radix select.
 //
 // One workgroup owns one score row.  Scores are mapped to unsigned keys whose
 // integer order is the float order, the n_keep-th largest key is found with
