@@ -9,6 +9,26 @@ namespace epicache {
 
 static size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Number of key splits for a kernel whose grid is `base` workgroups per split: the split count
+// (at most 32, at least 4 key tiles each) whose workgroup count fills whole rounds of the `slots`
+// workgroups the chip holds at once; `penalty` per split favours fewer splits.
+static void pick_splits(int64_t base, int64_t slots, int tiles, double penalty, int* n_splits,
+                        int* tiles_per_split) {
+  const int cap = tiles / 4 > 1 ? (tiles / 4 < 32 ? tiles / 4 : 32) : 1;
+  double best = -1.0;
+  int best_tps = tiles;
+  for (int s = 1; s <= cap; s++) {
+    const int tps = (tiles + s - 1) / s;
+    const int eff_s = (tiles + tps - 1) / tps;
+    const double rounds = (double)(base * eff_s) / (double)slots;
+    const double fill = rounds / (double)(int64_t)(rounds + 0.999999);
+    const double score = fill - penalty * eff_s;
+    if (score > best) best = score, best_tps = tps;
+  }
+  *tiles_per_split = best_tps;
+  *n_splits = (tiles + best_tps - 1) / best_tps;
+}
+
 int make_plan(const epicache_params* prm, Plan* out) {
   if (!prm || !out) return EPICACHE_ERR_INVALID_ARG;
   if (prm->struct_size != sizeof(epicache_params)) return EPICACHE_ERR_INVALID_ARG;
@@ -74,16 +94,17 @@ int make_plan(const epicache_params* prm, Plan* out) {
     else if (pl.R <= 128) pl.stats_rows_per_wg = 128;
     else pl.stats_rows_per_wg = ((pl.R + 191) / 192 * 192 < (pl.R + 255) / 256 * 256) ? 192 : 256;
     const int64_t base = nbh * ((pl.R + pl.stats_rows_per_wg - 1) / pl.stats_rows_per_wg);
-    int64_t want = (1024 + base - 1) / base;       // enough workgroups to fill 256 CUs
-    int64_t cap = tiles / 4 > 1 ? tiles / 4 : 1;   // at least 4 key tiles per workgroup
-    if (want > cap) want = cap;
-    if (want > 64) want = 64;
-    if (want < 1) want = 1;
-    pl.tiles_per_split = (int)((tiles + want - 1) / want);
-    pl.n_splits = (tiles + pl.tiles_per_split - 1) / pl.tiles_per_split;
+    // workgroups that fit the chip at once: 8 waves per CU (2 per SIMD), 256 CUs
+    const int nw = pl.stats_rows_per_wg == 192 ? 2 : pl.stats_rows_per_wg == 64 ? 2 : pl.stats_rows_per_wg == 32 ? 1 : 4;
+    const int64_t slots = 256 * (8 / nw);
+    pick_splits(base, slots, tiles, 0.004, &pl.n_splits, &pl.tiles_per_split);
+    // the streaming reduction re-derives every row's log-sum-exp per workgroup: fewer, longer splits
+    pick_splits(nbh, slots, tiles, 0.03, &pl.reduce_splits, &pl.reduce_tiles_per_split);
   } else {
     pl.n_splits = 1;
     pl.tiles_per_split = 0;
+    pl.reduce_splits = 1;
+    pl.reduce_tiles_per_split = 0;
   }
 
   size_t off = 0;

@@ -82,7 +82,7 @@ hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
   const int row_chunks = pl.d * pl.elem / 16;  // 16-byte chunks per row (head_dim % 8 == 0)
   const int64_t problems = (int64_t)pl.nb * pl.Hkv * 2;
   int slices = 1;
-  while (problems * slices < 1024 && row_chunks % (slices * 2) == 0 && row_chunks / (slices * 2) >= 4)
+  while (problems * slices < 1024 && row_chunks % (slices * 2) == 0 && row_chunks / (slices * 2) >= 8)
     slices *= 2;
   const int tpr = row_chunks / slices;
   hipLaunchKernelGGL(compact_rows, dim3((unsigned)(problems * slices)), dim3(256), 0, stream,

@@ -27,6 +27,8 @@ struct Plan {
   int stats_rows_per_wg;  // query rows per workgroup of the row-statistics pass
   int n_splits;     // key splits of the row-statistics pass
   int tiles_per_split;
+  int reduce_splits;  // key splits of the streaming reduction pass
+  int reduce_tiles_per_split;
   // workspace layout (byte offsets, 256-aligned)
   size_t off_stats, off_scores, off_keep, ws_total;
 };

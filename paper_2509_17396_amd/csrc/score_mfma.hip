@@ -84,12 +84,13 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)LDS_PTR(p);
 }
 
-// Staging of one 64-row tile, global -> LDS, by NW waves.  Rows are `stride` bytes apart.
+// Staging of one ROWS-row tile, global -> LDS, by NW waves.  Rows are `stride` bytes apart.
 // Wave w issues the 1 KiB slabs w, w + NW, w + 2*NW, ...; `wave` must be wave-uniform.
-template <int HD, int NW>
+template <int HD, int NW, int ROWS = 64>
 struct Stager {
   using TL = Tile<HD>;
-  static constexpr int kPer = (TL::kSlabs + NW - 1) / NW;  // direct loads per wave and tile (at most)
+  static constexpr int kSlabs = ROWS * TL::kRowBytes / 1024;  // 1 KiB wave-wide direct loads per tile
+  static constexpr int kPer = (kSlabs + NW - 1) / NW;          // direct loads per wave and tile (at most)
   // byte offset, from the first row of a tile, of the chunk that lane `lane` fetches in load i
   __device__ static __forceinline__ void offsets(uint32_t (&off)[kPer], int wave, int lane, uint32_t stride) {
 #pragma unroll
@@ -103,7 +104,7 @@ struct Stager {
                                              const uint32_t (&off)[kPer], int wave) {
 #pragma unroll
     for (int i = 0; i < kPer; i++)
-      if (TL::kSlabs % NW == 0 || wave + i * NW < TL::kSlabs)
+      if (kSlabs % NW == 0 || wave + i * NW < kSlabs)
         dma16_uniform_base(lds_tile + (wave + i * NW) * 1024, base, off[i]);
   }
   // general form: `row_ptr(r)` gives the address of row r of the tile (clamping, ragged strides)
@@ -111,7 +112,7 @@ struct Stager {
   __device__ static __forceinline__ void run_rows(uint32_t lds_tile, int wave, int lane, RowPtr row_ptr) {
 #pragma unroll
     for (int i = 0; i < kPer; i++) {
-      if (TL::kSlabs % NW == 0 || wave + i * NW < TL::kSlabs) {
+      if (kSlabs % NW == 0 || wave + i * NW < kSlabs) {
         const int row = (wave + i * NW) * TL::kRowsPerSlab + lane / TL::kChunks;
         dma16_lane_ptr(lds_tile + (wave + i * NW) * 1024,
                        row_ptr(row) + (((lane % TL::kChunks) ^ TL::swz(row)) * 16));
@@ -157,6 +158,30 @@ __device__ __forceinline__ void stats_begin(const f32x16& P, const RowStat& st, 
   corr = ex2((st.m - mn) * c2);  // exactly 1 when the max did not move
 }
 
+// Which accumulator values each MFMA slot of a unit works on while that MFMA executes: an MFMA
+// leaves the issue port free for roughly half of its 32 clocks, so the arithmetic is spread as
+// evenly as possible over the KS slots instead of being bunched behind the first few.
+template <int KS> struct Slots;
+template <> struct Slots<8> {
+  static constexpr int stats[9] = {0, 0, 2, 4, 6, 8, 11, 14, 16};   // slot 0 finds the new maximum
+  static constexpr int reduce[9] = {0, 2, 4, 6, 8, 10, 12, 14, 16};
+};
+template <> struct Slots<4> {
+  static constexpr int stats[5] = {0, 0, 5, 10, 16};
+  static constexpr int reduce[5] = {0, 4, 8, 12, 16};
+};
+
+template <int LO, int HI>
+__device__ __forceinline__ float stats_values(const f32x16& P, float c2, float nmc) {
+  float s = 0.f;
+#pragma unroll
+  for (int v = LO; v < HI; v++) {
+    const float e = ex2(fmaf(P[v], c2, nmc));
+    s = v == LO ? e : s + e;
+  }
+  return s;
+}
+
 __device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, float nmc) {
   const float e0 = ex2(fmaf(P[4 * g + 0], c2, nmc)), e1 = ex2(fmaf(P[4 * g + 1], c2, nmc));
   const float e2 = ex2(fmaf(P[4 * g + 2], c2, nmc)), e3 = ex2(fmaf(P[4 * g + 3], c2, nmc));
@@ -165,38 +190,37 @@ __device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, f
 
 // acc <- MFMA chain over head_dim (A rows = a-frag rows, B columns = b-frag rows), interleaved
 // with folding P, the tile finished one unit earlier, into its row statistics.
+template <int KS, int J>
+__device__ __forceinline__ void stats_slot(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
+                                           const f32x16& P, float c2, float nmc, float& sum) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], acc, 0, 0, 0);
+  fence_sched();
+  float part = stats_values<Slots<KS>::stats[J], Slots<KS>::stats[J + 1]>(P, c2, nmc);
+  pin(part);
+  sum += part;
+  fence_sched();
+}
+
 template <int KS>
 __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                            const f32x16& P, RowStat& st, float c2) {
-  float mn, nmc, corr, s0, s1, s2, s3;
+  float mn, nmc, corr, sum = 0.f;
   const f32x16 zero = {0};
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
+  fence_sched();
   stats_begin(P, st, c2, mn, nmc, corr);
   pin(nmc), pin(corr);
   fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
-  s0 = stats_group(P, 0, c2, nmc);
-  pin(s0);
-  fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], acc, 0, 0, 0);
-  s1 = stats_group(P, 1, c2, nmc);
-  pin(s1);
-  fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], acc, 0, 0, 0);
-  s2 = stats_group(P, 2, c2, nmc);
-  pin(s2);
-  fence_sched();
-  if (KS > 4) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[KS > 4 ? 4 : 0], b[KS > 4 ? 4 : 0], acc, 0, 0, 0);
-    s3 = stats_group(P, 3, c2, nmc);
-    pin(s3);
-    fence_sched();
-#pragma unroll
-    for (int j = 5; j < KS; j++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc, 0, 0, 0);
-  } else {
-    s3 = stats_group(P, 3, c2, nmc);
+  stats_slot<KS, 1>(acc, a, b, P, c2, nmc, sum);
+  stats_slot<KS, 2>(acc, a, b, P, c2, nmc, sum);
+  stats_slot<KS, 3>(acc, a, b, P, c2, nmc, sum);
+  if constexpr (KS == 8) {
+    stats_slot<KS, 4>(acc, a, b, P, c2, nmc, sum);
+    stats_slot<KS, 5>(acc, a, b, P, c2, nmc, sum);
+    stats_slot<KS, 6>(acc, a, b, P, c2, nmc, sum);
+    stats_slot<KS, 7>(acc, a, b, P, c2, nmc, sum);
   }
-  st.D = fmaf(st.D, corr, (s0 + s1) + (s2 + s3));
+  st.D = fmaf(st.D, corr, sum);
   st.m = mn;
   fence_sched();
 }
@@ -357,31 +381,43 @@ __device__ __forceinline__ float col_merge(float col, float a, float b, float c,
   return col + ((a + b) + (c + d));
 }
 
+template <int REDUCE, int LO, int HI>
+__device__ __forceinline__ float col_values(const f32x16& P, const float (&nl)[16], float c2) {
+  float s = 0.f;
+#pragma unroll
+  for (int v = LO; v < HI; v++) {
+    const float x = fmaf(P[v], c2, nl[v]);
+    if (REDUCE == EPICACHE_REDUCE_MAX) s = v == LO ? x : fmaxf(s, x);
+    else s = v == LO ? ex2(x) : s + ex2(x);
+  }
+  return s;
+}
+
+template <int KS, int REDUCE, int J>
+__device__ __forceinline__ void reduce_slot(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
+                                            const f32x16& P, const float (&nl)[16], float& col, float c2) {
+  const f32x16 zero = {0};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], J == 0 ? zero : acc, 0, 0, 0);
+  fence_sched();
+  float part = col_values<REDUCE, Slots<KS>::reduce[J], Slots<KS>::reduce[J + 1]>(P, nl, c2);
+  pin(part);
+  col = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(col, part) : col + part;
+  fence_sched();
+}
+
 template <int KS, int REDUCE>
 __device__ __forceinline__ void reduce_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                             const f32x16& P, const float (&nl)[16], float& col, float c2) {
-  float s0, s1, s2, s3;
-  const f32x16 zero = {0};
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
-  s0 = col_group<REDUCE>(P, nl, 0, c2);
-  pin(s0);
-  fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], acc, 0, 0, 0);
-  s1 = col_group<REDUCE>(P, nl, 1, c2);
-  pin(s1);
-  fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], acc, 0, 0, 0);
-  s2 = col_group<REDUCE>(P, nl, 2, c2);
-  pin(s2);
-  fence_sched();
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], acc, 0, 0, 0);
-  s3 = col_group<REDUCE>(P, nl, 3, c2);
-  col = col_merge<REDUCE>(col, s0, s1, s2, s3);
-  pin(col);
-  fence_sched();
-#pragma unroll
-  for (int j = 4; j < KS; j++) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc, 0, 0, 0);
-  fence_sched();
+  reduce_slot<KS, REDUCE, 0>(acc, a, b, P, nl, col, c2);
+  reduce_slot<KS, REDUCE, 1>(acc, a, b, P, nl, col, c2);
+  reduce_slot<KS, REDUCE, 2>(acc, a, b, P, nl, col, c2);
+  reduce_slot<KS, REDUCE, 3>(acc, a, b, P, nl, col, c2);
+  if constexpr (KS == 8) {
+    reduce_slot<KS, REDUCE, 4>(acc, a, b, P, nl, col, c2);
+    reduce_slot<KS, REDUCE, 5>(acc, a, b, P, nl, col, c2);
+    reduce_slot<KS, REDUCE, 6>(acc, a, b, P, nl, col, c2);
+    reduce_slot<KS, REDUCE, 7>(acc, a, b, P, nl, col, c2);
+  }
 }
 
 __device__ __forceinline__ void read_nlse(float (&nl)[16], const float* nlse, int row0, int hi) {
@@ -550,8 +586,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   const float c2 = pl.c2;
 
   const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
-  const int t_begin = split * pl.tiles_per_split;
-  const int t_end = min(tiles, t_begin + pl.tiles_per_split);
+  const int t_begin = split * pl.reduce_tiles_per_split;
+  const int t_end = min(tiles, t_begin + pl.reduce_tiles_per_split);
 
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(k + b * pl.ksb + (int64_t)h * pl.ksh);
   const uint32_t kstride = (uint32_t)pl.kst * 2;
@@ -657,7 +693,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
 template <int HD, int NQ, int NW>
 void launch_reduce_stream(const Plan& pl, const bf16_t* q, const bf16_t* k, const float2* stats,
                           float* scores, hipStream_t stream) {
-  dim3 grid(pl.n_splits, pl.nb * pl.Hkv);
+  dim3 grid(pl.reduce_splits, pl.nb * pl.Hkv);
   if (pl.reduce == EPICACHE_REDUCE_MAX)
     hipLaunchKernelGGL((score_reduce_stream<HD, NQ, NW, EPICACHE_REDUCE_MAX>), grid, dim3(NW * 64), 0,
                        stream, q, k, stats, scores, pl);
