@@ -101,3 +101,21 @@ def test_binding_raises_with_status():
     with pytest.raises(ep.EpicacheError) as ei:
         ep.epicache_workspace_size(_params(budget=-3))
     assert ei.value.status == ep.ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: without the built HIP library the binding raises."""
+    monkeypatch.setattr(ep, "_lib", None)
+    monkeypatch.setattr(ep, "_LIB_PATH", str(tmp_path / "libepicache.so"))
+    with pytest.raises(FileNotFoundError):
+        ep.load()
+    with pytest.raises(FileNotFoundError):
+        ep.epicache_workspace_size(_params())
+
+
+def test_product_package_never_imports_the_oracle():
+    import pathlib
+    pkg = pathlib.Path(ROOT) / "paper_2509_17396_amd"
+    for path in list(pkg.rglob("*.py")) + list(pkg.rglob("*.hip")) + list(pkg.rglob("*.h")):
+        text = path.read_text()
+        assert "oracle" not in text.lower() or path.name == "synth.py", path
