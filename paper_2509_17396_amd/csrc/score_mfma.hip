@@ -158,28 +158,52 @@ __device__ __forceinline__ void stats_begin(const f32x16& P, const RowStat& st, 
   corr = ex2((st.m - mn) * c2);  // exactly 1 when the max did not move
 }
 
-// Which accumulator values each MFMA slot of a unit works on while that MFMA executes: an MFMA
-// leaves the issue port free for roughly half of its 32 clocks, so the arithmetic is spread as
-// evenly as possible over the KS slots instead of being bunched behind the first few.
+// Which accumulator values enter the arithmetic pipeline in each MFMA slot of a unit.  An MFMA
+// leaves the issue port free for about half of its 32 clocks, so the softmax arithmetic is spread
+// evenly over the KS slots; and because dependent VALU / transcendental ops have several clocks of
+// latency, it is staggered: the values that get their multiply-add in slot j get their exp2 in
+// slot j+1 and are summed in slot j+2, so the instructions inside one slot never wait on each other.
 template <int KS> struct Slots;
 template <> struct Slots<8> {
-  static constexpr int stats[9] = {0, 0, 2, 4, 6, 8, 11, 14, 16};   // slot 0 finds the new maximum
+  static constexpr int stats[9] = {0, 0, 3, 6, 8, 10, 12, 14, 16};  // slot 0 finds the new maximum
   static constexpr int reduce[9] = {0, 2, 4, 6, 8, 10, 12, 14, 16};
 };
 template <> struct Slots<4> {
-  static constexpr int stats[5] = {0, 0, 5, 10, 16};
+  static constexpr int stats[5] = {0, 0, 6, 11, 16};
   static constexpr int reduce[5] = {0, 4, 8, 12, 16};
 };
 
+// pipeline stages over the value range [LO, HI); each pins its results at the point of issue
 template <int LO, int HI>
-__device__ __forceinline__ float stats_values(const f32x16& P, float c2, float nmc) {
-  float s = 0.f;
+__device__ __forceinline__ void stage_exp(float (&x)[16]) {
+#pragma unroll
+  for (int v = LO; v < HI; v++) x[v] = ex2(x[v]);
+#pragma unroll
+  for (int v = LO; v < HI; v++) pin(x[v]);
+}
+template <int LO, int HI>
+__device__ __forceinline__ void stage_add(const float (&x)[16], float& s0, float& s1) {
 #pragma unroll
   for (int v = LO; v < HI; v++) {
-    const float e = ex2(fmaf(P[v], c2, nmc));
-    s = v == LO ? e : s + e;
+    if (v & 1) s1 += x[v]; else s0 += x[v];
   }
-  return s;
+  if (HI > LO) pin(s0), pin(s1);
+}
+template <int LO, int HI>
+__device__ __forceinline__ void stage_max(const float (&x)[16], float& s0, float& s1) {
+#pragma unroll
+  for (int v = LO; v < HI; v++) {
+    if (v & 1) s1 = fmaxf(s1, x[v]); else s0 = fmaxf(s0, x[v]);
+  }
+  if (HI > LO) pin(s0), pin(s1);
+}
+
+template <int LO, int HI>
+__device__ __forceinline__ void stats_stage_fma(float (&x)[16], const f32x16& P, float c2, float nmc) {
+#pragma unroll
+  for (int v = LO; v < HI; v++) x[v] = fmaf(P[v], c2, nmc);
+#pragma unroll
+  for (int v = LO; v < HI; v++) pin(x[v]);
 }
 
 __device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, float nmc) {
@@ -192,35 +216,42 @@ __device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, f
 // with folding P, the tile finished one unit earlier, into its row statistics.
 template <int KS, int J>
 __device__ __forceinline__ void stats_slot(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
-                                           const f32x16& P, float c2, float nmc, float& sum) {
+                                           const f32x16& P, float c2, float nmc, float (&x)[16], float& s0,
+                                           float& s1) {
+  using SL = Slots<KS>;
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], acc, 0, 0, 0);
   fence_sched();
-  float part = stats_values<Slots<KS>::stats[J], Slots<KS>::stats[J + 1]>(P, c2, nmc);
-  pin(part);
-  sum += part;
+  stats_stage_fma<SL::stats[J], SL::stats[J + 1]>(x, P, c2, nmc);
+  stage_exp<SL::stats[J - 1], SL::stats[J]>(x);
+  if constexpr (J >= 2) stage_add<SL::stats[J - 2], SL::stats[J - 1]>(x, s0, s1);
   fence_sched();
 }
 
 template <int KS>
 __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                            const f32x16& P, RowStat& st, float c2) {
-  float mn, nmc, corr, sum = 0.f;
+  using SL = Slots<KS>;
+  float mn, nmc, corr, s0 = 0.f, s1 = 0.f, x[16];
   const f32x16 zero = {0};
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
   fence_sched();
   stats_begin(P, st, c2, mn, nmc, corr);
   pin(nmc), pin(corr);
   fence_sched();
-  stats_slot<KS, 1>(acc, a, b, P, c2, nmc, sum);
-  stats_slot<KS, 2>(acc, a, b, P, c2, nmc, sum);
-  stats_slot<KS, 3>(acc, a, b, P, c2, nmc, sum);
+  stats_slot<KS, 1>(acc, a, b, P, c2, nmc, x, s0, s1);
+  stats_slot<KS, 2>(acc, a, b, P, c2, nmc, x, s0, s1);
+  stats_slot<KS, 3>(acc, a, b, P, c2, nmc, x, s0, s1);
   if constexpr (KS == 8) {
-    stats_slot<KS, 4>(acc, a, b, P, c2, nmc, sum);
-    stats_slot<KS, 5>(acc, a, b, P, c2, nmc, sum);
-    stats_slot<KS, 6>(acc, a, b, P, c2, nmc, sum);
-    stats_slot<KS, 7>(acc, a, b, P, c2, nmc, sum);
+    stats_slot<KS, 4>(acc, a, b, P, c2, nmc, x, s0, s1);
+    stats_slot<KS, 5>(acc, a, b, P, c2, nmc, x, s0, s1);
+    stats_slot<KS, 6>(acc, a, b, P, c2, nmc, x, s0, s1);
+    stats_slot<KS, 7>(acc, a, b, P, c2, nmc, x, s0, s1);
   }
-  st.D = fmaf(st.D, corr, sum);
+  // drain the pipeline: last exp2 stage, last two sum stages
+  stage_exp<SL::stats[KS - 1], SL::stats[KS]>(x);
+  stage_add<SL::stats[KS - 2], SL::stats[KS - 1]>(x, s0, s1);
+  stage_add<SL::stats[KS - 1], SL::stats[KS]>(x, s0, s1);
+  st.D = fmaf(st.D, corr, s0 + s1);
   st.m = mn;
   fence_sched();
 }
@@ -381,43 +412,60 @@ __device__ __forceinline__ float col_merge(float col, float a, float b, float c,
   return col + ((a + b) + (c + d));
 }
 
-template <int REDUCE, int LO, int HI>
-__device__ __forceinline__ float col_values(const f32x16& P, const float (&nl)[16], float c2) {
-  float s = 0.f;
+template <int LO, int HI>
+__device__ __forceinline__ void col_stage_fma(float (&x)[16], const f32x16& P, const float (&nl)[16], float c2) {
 #pragma unroll
-  for (int v = LO; v < HI; v++) {
-    const float x = fmaf(P[v], c2, nl[v]);
-    if (REDUCE == EPICACHE_REDUCE_MAX) s = v == LO ? x : fmaxf(s, x);
-    else s = v == LO ? ex2(x) : s + ex2(x);
-  }
-  return s;
+  for (int v = LO; v < HI; v++) x[v] = fmaf(P[v], c2, nl[v]);
+#pragma unroll
+  for (int v = LO; v < HI; v++) pin(x[v]);
 }
 
 template <int KS, int REDUCE, int J>
 __device__ __forceinline__ void reduce_slot(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
-                                            const f32x16& P, const float (&nl)[16], float& col, float c2) {
+                                            const f32x16& P, const float (&nl)[16], float c2, float (&x)[16],
+                                            float& s0, float& s1) {
+  using SL = Slots<KS>;
   const f32x16 zero = {0};
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], J == 0 ? zero : acc, 0, 0, 0);
   fence_sched();
-  float part = col_values<REDUCE, Slots<KS>::reduce[J], Slots<KS>::reduce[J + 1]>(P, nl, c2);
-  pin(part);
-  col = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(col, part) : col + part;
+  col_stage_fma<SL::reduce[J], SL::reduce[J + 1]>(x, P, nl, c2);
+  if constexpr (REDUCE == EPICACHE_REDUCE_MAX) {
+    if constexpr (J >= 1) stage_max<SL::reduce[J - 1], SL::reduce[J]>(x, s0, s1);
+  } else {
+    if constexpr (J >= 1) stage_exp<SL::reduce[J - 1], SL::reduce[J]>(x);
+    if constexpr (J >= 2) stage_add<SL::reduce[J - 2], SL::reduce[J - 1]>(x, s0, s1);
+  }
   fence_sched();
 }
 
+// acc <- MFMA chain, interleaved with reducing P (the tile finished one unit earlier; nl = minus the
+// base-2 log-sum-exp of each of its 16 rows) into `col`.
 template <int KS, int REDUCE>
 __device__ __forceinline__ void reduce_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                             const f32x16& P, const float (&nl)[16], float& col, float c2) {
-  reduce_slot<KS, REDUCE, 0>(acc, a, b, P, nl, col, c2);
-  reduce_slot<KS, REDUCE, 1>(acc, a, b, P, nl, col, c2);
-  reduce_slot<KS, REDUCE, 2>(acc, a, b, P, nl, col, c2);
-  reduce_slot<KS, REDUCE, 3>(acc, a, b, P, nl, col, c2);
+  using SL = Slots<KS>;
+  float x[16];
+  float s0 = REDUCE == EPICACHE_REDUCE_MAX ? -INFINITY : 0.f, s1 = s0;
+  reduce_slot<KS, REDUCE, 0>(acc, a, b, P, nl, c2, x, s0, s1);
+  reduce_slot<KS, REDUCE, 1>(acc, a, b, P, nl, c2, x, s0, s1);
+  reduce_slot<KS, REDUCE, 2>(acc, a, b, P, nl, c2, x, s0, s1);
+  reduce_slot<KS, REDUCE, 3>(acc, a, b, P, nl, c2, x, s0, s1);
   if constexpr (KS == 8) {
-    reduce_slot<KS, REDUCE, 4>(acc, a, b, P, nl, col, c2);
-    reduce_slot<KS, REDUCE, 5>(acc, a, b, P, nl, col, c2);
-    reduce_slot<KS, REDUCE, 6>(acc, a, b, P, nl, col, c2);
-    reduce_slot<KS, REDUCE, 7>(acc, a, b, P, nl, col, c2);
+    reduce_slot<KS, REDUCE, 4>(acc, a, b, P, nl, c2, x, s0, s1);
+    reduce_slot<KS, REDUCE, 5>(acc, a, b, P, nl, c2, x, s0, s1);
+    reduce_slot<KS, REDUCE, 6>(acc, a, b, P, nl, c2, x, s0, s1);
+    reduce_slot<KS, REDUCE, 7>(acc, a, b, P, nl, c2, x, s0, s1);
   }
+  if constexpr (REDUCE == EPICACHE_REDUCE_MAX) {
+    stage_max<SL::reduce[KS - 1], SL::reduce[KS]>(x, s0, s1);
+    col = max3(col, s0, s1);
+  } else {
+    stage_exp<SL::reduce[KS - 1], SL::reduce[KS]>(x);
+    stage_add<SL::reduce[KS - 2], SL::reduce[KS - 1]>(x, s0, s1);
+    stage_add<SL::reduce[KS - 1], SL::reduce[KS]>(x, s0, s1);
+    col += s0 + s1;
+  }
+  fence_sched();
 }
 
 __device__ __forceinline__ void read_nlse(float (&nl)[16], const float* nlse, int row0, int hi) {
