@@ -90,6 +90,17 @@ EPICACHE_API int epicache_workspace_size(const epicache_params* params, size_t* 
 EPICACHE_API int epicache_score(const epicache_params* params, const void* q, const void* k,
                    float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Sec. 2.3, Eq. 1 with every scoring query's softmax normaliser supplied by the caller: the same
+ * scores as epicache_score, computed in a single pass over K.  row_lse [n_batch, n_q_heads,
+ * patch_len] float32, dense, read only: natural logarithm of the sum of exp(scale * q.k) over all
+ * keys that query attended to, as a fused attention kernel returns it for the patched prompt's
+ * forward pass.  If that sum runs over more keys than the N context rows (the patch's own causal
+ * keys), the scores are the attention weights under that larger denominator.  Needs the same
+ * workspace as epicache_score. */
+EPICACHE_API int epicache_score_lse(const epicache_params* params, const void* q, const void* k,
+                   const float* row_lse, float* scores, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
+
 /* Sec. 3.1 Stage 2 / Alg. 1 phase A3 (retention of the M best-scoring tokens).  For every
  * (b, h): the n_keep = min(budget, N) rows with the largest score, written in
  * ascending row order.  Equal scores: the lower row index wins.  Scores are

@@ -68,6 +68,31 @@ def score(q: np.ndarray, k: np.ndarray, n_ctx: int, reduce: int = REDUCE_MAX,
     return out
 
 
+def score_given_lse(q: np.ndarray, k: np.ndarray, n_ctx: int, row_lse: np.ndarray, reduce: int = REDUCE_MAX,
+                    scale: float | None = None) -> np.ndarray:
+    """Eq. 1 when every scoring query's softmax normaliser is supplied from outside.
+
+    row_lse [nb, Hq, p]: natural log of the sum of exp(scale * q.k) over all keys that query attends
+    to.  If that set is the N context keys this equals score(); if it is larger (in a real forward
+    pass patch token t also attends to the patch tokens up to t, Sec. 2.3) the result is the
+    attention weight under that larger denominator, restricted to the context columns.
+    """
+    nb, Hq, p, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((nb, Hkv, n_ctx), dtype=np.float64)
+    for b in range(nb):
+        for h in range(Hkv):
+            rows = np.asarray(q[b, h * G:(h + 1) * G], dtype=np.float64).reshape(G * p, d)
+            lse = np.asarray(row_lse[b, h * G:(h + 1) * G], dtype=np.float64).reshape(G * p, 1)
+            keys = np.asarray(k[b, h, :n_ctx], dtype=np.float64)
+            attn = np.exp(scale * (rows @ keys.T) - lse)
+            out[b, h] = attn.max(axis=0) if reduce == REDUCE_MAX else attn.sum(axis=0)
+    return out
+
+
 def topk_1d(s: np.ndarray, M: int) -> np.ndarray:
     """Indices of the min(M, N) largest entries of s, ascending; ties -> lower index."""
     N = s.shape[0]

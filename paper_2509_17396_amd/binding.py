@@ -21,7 +21,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 REDUCE_MAX, REDUCE_SUM = 0, 1
 
 ENTRY_POINTS = (
-    "epicache_workspace_size", "epicache_score", "epicache_topk", "epicache_compact",
+    "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_status_string", "epicache_version",
 )
 
@@ -77,10 +77,11 @@ def load() -> ctypes.CDLL:
     pp = ctypes.POINTER(Params)
     lib.epicache_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
     lib.epicache_score.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_score_lse.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.epicache_compact.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
-    for name in ENTRY_POINTS[:5]:
+    for name in ENTRY_POINTS[:6]:
         getattr(lib, name).restype = i32
     lib.epicache_status_string.argtypes = [i32]
     lib.epicache_status_string.restype = ctypes.c_char_p
@@ -136,6 +137,11 @@ def alloc_workspace(params: Params, device="cuda") -> torch.Tensor:
 def epicache_score(params: Params, q, k, scores, workspace) -> None:
     _check(load().epicache_score(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(scores),
                                  _ptr(workspace), workspace.numel(), _stream()), "epicache_score")
+
+
+def epicache_score_lse(params: Params, q, k, row_lse, scores, workspace) -> None:
+    _check(load().epicache_score_lse(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(row_lse), _ptr(scores),
+                                     _ptr(workspace), workspace.numel(), _stream()), "epicache_score_lse")
 
 
 def epicache_topk(params: Params, scores, keep_idx, workspace=None) -> None:

@@ -124,8 +124,8 @@ static bool misaligned(const void* ptr) { return (reinterpret_cast<uintptr_t>(pt
 static int run_score(const Plan& pl, const void* q, const void* k, float* scores, char* ws,
                      hipStream_t stream) {
   float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
-  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, stream)
-                             : launch_score_generic(pl, q, k, scores, stats, stream);
+  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, false, stream)
+                             : launch_score_generic(pl, q, k, scores, stats, false, stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
@@ -154,6 +154,25 @@ int epicache_score(const epicache_params* params, const void* q, const void* k, 
     return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
   return run_score(pl, q, k, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
+}
+
+int epicache_score_lse(const epicache_params* params, const void* q, const void* k,
+                       const float* row_lse, float* scores, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !row_lse || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(row_lse) || misaligned(scores) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  pl.n_splits = 1;  // the caller's normalisers take the place of pass 1: one (max, sum) pair per row
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float2* stats = reinterpret_cast<float2*>(static_cast<char*>(workspace) + pl.off_stats);
+  if (launch_lse_to_stats(pl, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, true, stream)
+                             : launch_score_generic(pl, q, k, scores, stats, true, stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
 int epicache_topk(const epicache_params* params, const float* scores, int32_t* keep_idx,

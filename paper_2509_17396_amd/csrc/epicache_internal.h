@@ -39,10 +39,12 @@ constexpr int kKeysPerWG = 256;  // keys per workgroup in the reduction pass
 int make_plan(const epicache_params* prm, Plan* out);
 
 // Each launcher enqueues on `stream` and returns a hipError_t.
+// `stats_ready`: the row statistics are already in `stats` (one split); only the reduction pass runs.
 hipError_t launch_score_generic(const Plan& pl, const void* q, const void* k, float* scores,
-                                float2* stats, hipStream_t stream);
+                                float2* stats, bool stats_ready, hipStream_t stream);
 hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float* scores,
-                             float2* stats, hipStream_t stream);
+                             float2* stats, bool stats_ready, hipStream_t stream);
+hipError_t launch_lse_to_stats(const Plan& pl, const float* row_lse, float2* stats, hipStream_t stream);
 hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipStream_t stream);
 hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);
 hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,

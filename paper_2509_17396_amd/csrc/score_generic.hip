@@ -95,13 +95,24 @@ __global__ __launch_bounds__(256) void score_generic_reduce(const T* __restrict_
   }
 }
 
+// Caller-supplied natural-log normalisers -> the (base-2 max, sum) pairs the reduction pass reads.
+// Rows of one KV head are contiguous in row_lse: (b*Hq + h*G + g)*p + t = (b*Hkv + h)*R + g*p + t.
+__global__ void lse_to_stats(const float* __restrict__ row_lse, float2* __restrict__ stats, int R, int Rpad,
+                             size_t total) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const size_t bh = i / R;
+  const int r = (int)(i % R);
+  stats[bh * Rpad + r] = make_float2(row_lse[i] * 1.44269504088896340736f, 1.0f);
+}
+
 template <typename T>
-hipError_t launch_t(const Plan& pl, const T* q, const T* k, float* scores, float2* stats,
+hipError_t launch_t(const Plan& pl, const T* q, const T* k, float* scores, float2* stats, bool stats_ready,
                     hipStream_t stream) {
   const int nbh = pl.nb * pl.Hkv;
   dim3 g1((pl.R + 3) / 4, nbh), g2((pl.N + 31) / 32, nbh);
   const size_t smem = (size_t)(32 * (pl.d + 1) + 8 * 32) * sizeof(float);
-  hipLaunchKernelGGL(score_generic_stats<T>, g1, dim3(256), 0, stream, q, k, stats, pl);
+  if (!stats_ready) hipLaunchKernelGGL(score_generic_stats<T>, g1, dim3(256), 0, stream, q, k, stats, pl);
   if (pl.reduce == EPICACHE_REDUCE_MAX)
     hipLaunchKernelGGL((score_generic_reduce<T, EPICACHE_REDUCE_MAX>), g2, dim3(256), smem, stream,
                        q, k, stats, scores, pl);
@@ -114,12 +125,19 @@ hipError_t launch_t(const Plan& pl, const T* q, const T* k, float* scores, float
 }  // namespace
 
 hipError_t launch_score_generic(const Plan& pl, const void* q, const void* k, float* scores,
-                                float2* stats, hipStream_t stream) {
+                                float2* stats, bool stats_ready, hipStream_t stream) {
   if (pl.dtype == EPICACHE_DTYPE_F32)
     return launch_t<float>(pl, static_cast<const float*>(q), static_cast<const float*>(k), scores,
-                           stats, stream);
+                           stats, stats_ready, stream);
   return launch_t<__hip_bfloat16>(pl, static_cast<const __hip_bfloat16*>(q),
-                                  static_cast<const __hip_bfloat16*>(k), scores, stats, stream);
+                                  static_cast<const __hip_bfloat16*>(k), scores, stats, stats_ready, stream);
+}
+
+hipError_t launch_lse_to_stats(const Plan& pl, const float* row_lse, float2* stats, hipStream_t stream) {
+  const size_t total = (size_t)pl.nb * pl.Hkv * pl.R;
+  hipLaunchKernelGGL(lse_to_stats, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, row_lse,
+                     stats, pl.R, pl.Rpad, total);
+  return hipGetLastError();
 }
 
 }  // namespace epicache

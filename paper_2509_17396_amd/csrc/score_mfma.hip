@@ -759,10 +759,10 @@ void launch_stats(const Plan& pl, const bf16_t* q, const bf16_t* k, float2* stat
 
 template <int HD>
 hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* scores,
-                     float2* stats, hipStream_t stream) {
+                     float2* stats, bool stats_ready, hipStream_t stream) {
   using TL = Tile<HD>;
   const int nbh = pl.nb * pl.Hkv;
-  switch (pl.stats_rows_per_wg) {
+  if (!stats_ready) switch (pl.stats_rows_per_wg) {
     case 256: launch_stats<HD, 2, 4>(pl, q, k, stats, stream); break;
     case 192: launch_stats<HD, 3, 2>(pl, q, k, stats, stream); break;
     case 128: launch_stats<HD, 1, 4>(pl, q, k, stats, stream); break;
@@ -793,11 +793,11 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
 }  // namespace
 
 hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float* scores,
-                             float2* stats, hipStream_t stream) {
+                             float2* stats, bool stats_ready, hipStream_t stream) {
   const bf16_t* qq = static_cast<const bf16_t*>(q);
   const bf16_t* kk = static_cast<const bf16_t*>(k);
-  if (pl.d == 128) return launch_hd<128>(pl, qq, kk, scores, stats, stream);
-  if (pl.d == 64) return launch_hd<64>(pl, qq, kk, scores, stats, stream);
+  if (pl.d == 128) return launch_hd<128>(pl, qq, kk, scores, stats, stats_ready, stream);
+  if (pl.d == 64) return launch_hd<64>(pl, qq, kk, scores, stats, stats_ready, stream);
   return hipErrorInvalidValue;
 }
 

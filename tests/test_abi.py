@@ -73,6 +73,7 @@ def test_bad_params_are_rejected_before_any_launch(field, value, status):
     # the compute entry points validate params first, with the same result
     dummy = ctypes.c_void_p(4096)
     assert lib.epicache_score(ctypes.byref(prm), dummy, dummy, dummy, dummy, 1 << 30, None) == status
+    assert lib.epicache_score_lse(ctypes.byref(prm), dummy, dummy, dummy, dummy, dummy, 1 << 30, None) == status
     assert lib.epicache_topk(ctypes.byref(prm), dummy, dummy, None, 0, None) == status
     assert lib.epicache_compact(ctypes.byref(prm), dummy, dummy, ctypes.c_void_p(8192), None, 0, None) == status
     assert lib.epicache_evict_step(ctypes.byref(prm), dummy, dummy, ctypes.c_void_p(8192), None, None,
@@ -89,6 +90,8 @@ def test_null_misaligned_and_small_workspace_are_rejected():
     assert lib.epicache_score(ctypes.byref(prm), None, a, a, a, need, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_score(ctypes.byref(prm), a, c, a, a, need, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_score(ctypes.byref(prm), a, a, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_score_lse(ctypes.byref(prm), a, a, None, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score_lse(ctypes.byref(prm), a, a, a, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
     assert lib.epicache_topk(ctypes.byref(prm), a, None, None, 0, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_compact(ctypes.byref(prm), a, a, a, None, 0, None) == ep.ERR_INVALID_ARG  # K is V
     assert lib.epicache_compact(ctypes.byref(prm), a, a, None, None, 0, None) == ep.ERR_INVALID_ARG

@@ -104,6 +104,46 @@ def test_score_mfma_agrees_with_generic_kernel_closely():
     np.testing.assert_allclose(a, b, rtol=1e-3, atol=pu.ATOL)
 
 
+# ------------------------------------------------- score with supplied normalisers
+
+LSE_CASES = [
+    ("fp32_tiny", "tiny", {}, None),
+    ("bf16_stream_R192", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=64), 1000),
+    ("bf16_keys_stationary_R400", "llama31_8b", dict(E=1, Hq=8, Hkv=2, p=100), 777),
+    ("bf16_generic_d96", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=9, d=96), 150),
+]
+
+
+@pytest.mark.parametrize("extra_keys", [0, 40], ids=["context_only", "larger_denominator"])
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+@pytest.mark.parametrize("case", LSE_CASES, ids=[c[0] for c in LSE_CASES])
+def test_score_lse_matches_oracle(case, reduce, extra_keys):
+    """epicache_score_lse: one pass over K with the row normalisers handed in.  With extra_keys the
+    normaliser also covers keys beyond the N context rows (as the patch's own keys would be)."""
+    import scipy.special
+    name, base, over, n_ctx = case
+    w = wl(base, **over)
+    N = w.N if n_ctx is None else n_ctx
+    say(f"score_lse {name} reduce={reduce} N={N} extra={extra_keys}")
+    q, k, _ = synth.make_layer(w, layer=2, n_ctx=N, capacity=N + extra_keys)
+    qq, kk = pu.oracle_inputs(q, k)
+    G = w.G
+    scale = 1.0 / w.d ** 0.5
+    # normaliser over the first N + extra_keys rows of K, float64, handed over as float32
+    z = scale * np.einsum("bhtd,bhnd->bhtn", qq, np.repeat(kk[:, :, :N + extra_keys], G, axis=1))
+    lse32 = scipy.special.logsumexp(z, axis=3).astype(np.float32)
+    qd, kd = q.to(DEV), k.to(DEV)
+    prm = ep.make_params(qd, kd, n_cached=min(w.M, N), n_block=N - min(w.M, N), budget=w.M, reduce=reduce)
+    ws = ep.alloc_workspace(prm)
+    scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+    ep.epicache_score_lse(prm, qd, kd, torch.from_numpy(lse32).to(DEV), scores, ws)
+    torch.cuda.synchronize()
+    want = orc.score_given_lse(qq, kk, N, lse32.astype(np.float64), reduce)
+    pu.assert_scores_close(scores.cpu().numpy(), want, pu.rtol_for(q.dtype), name)
+    if extra_keys == 0:  # same thing as the two-pass entry point, to within the tolerance
+        pu.assert_scores_close(scores.cpu().numpy(), orc.score(qq, kk, N, reduce), pu.rtol_for(q.dtype), name)
+
+
 # -------------------------------------------------------------------- topk
 
 def gpu_topk(scores_np, M):

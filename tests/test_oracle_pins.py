@@ -179,6 +179,37 @@ def test_dominant_key_takes_all_the_mass():
     assert np.delete(smax, 4).max() < 1e-21
 
 
+def test_score_given_lse_reduces_to_score_and_to_the_closed_form():
+    rng = np.random.default_rng(31)
+    q = rng.standard_normal((2, 4, 3, 8))
+    k = rng.standard_normal((2, 2, 17, 8))
+    z = np.einsum("bhtd,bhnd->bhtn", q, np.repeat(k, 2, axis=1)) / math.sqrt(8)
+    lse = scipy.special.logsumexp(z, axis=3)                      # normaliser over exactly the context keys
+    for reduce in (orc.REDUCE_MAX, orc.REDUCE_SUM):
+        np.testing.assert_allclose(orc.score_given_lse(q, k, 17, lse, reduce), orc.score(q, k, 17, reduce), rtol=1e-12)
+    a, b, rows, red = _load_integer_powers()
+    keys = np.array([[math.log(x), math.log(y)] for x, y in zip(a, b)]).reshape(1, 1, 4, 2)
+    qq = np.array([r[0] for r in rows], dtype=np.float64).reshape(1, 2, 2, 2)
+    lse = np.log(np.array([10.0, 7.0, 19.0, 113.0 / 6.0])).reshape(1, 2, 2)   # denominators of the fixture rows
+    got = orc.score_given_lse(qq, keys, 4, lse, orc.REDUCE_SUM, scale=1.0)[0, 0]
+    np.testing.assert_allclose(got, [float(f) for f in red["sum"]], rtol=1e-13)
+
+
+def test_score_given_lse_with_a_larger_denominator_is_the_restricted_full_softmax():
+    """Normaliser taken over context keys plus extra keys (the patch's own keys in a real forward
+    pass): the result is the attention weight of the concatenated softmax on the context columns."""
+    rng = np.random.default_rng(37)
+    d, N, X = 8, 13, 5
+    q = rng.standard_normal((1, 1, 4, d))
+    k = rng.standard_normal((1, 1, N, d))
+    extra = rng.standard_normal((X, d))
+    full = orc.attention_weights(q[0, 0], np.concatenate([k[0, 0], extra]), 1 / math.sqrt(d))   # [4, N+X]
+    z_all = (q[0, 0] @ np.concatenate([k[0, 0], extra]).T) / math.sqrt(d)
+    lse = scipy.special.logsumexp(z_all, axis=1).reshape(1, 1, 4)
+    np.testing.assert_allclose(orc.score_given_lse(q, k, N, lse, orc.REDUCE_MAX)[0, 0], full[:, :N].max(axis=0), rtol=1e-12)
+    np.testing.assert_allclose(orc.score_given_lse(q, k, N, lse, orc.REDUCE_SUM)[0, 0], full[:, :N].sum(axis=0), rtol=1e-12)
+
+
 # ----------------------------------------------------------------- topk pins
 
 def test_topk_matches_counting_definition_with_ties():
