@@ -126,6 +126,16 @@ EPICACHE_API int epicache_evict_step(const epicache_params* params, const void* 
                         float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
+/* Sec. 3.2, Eq. 6 / Alg. 1 phase A2: split the global budget n_layers * budget over the layers in
+ * proportion to sensitivity[l]^alpha (sensitivity[l] = 1 - sigma_l >= 0, alpha >= 0 the sharpness).
+ * The paper's allocation is real-valued; here it is rounded by largest remainder (ties to the lower
+ * layer) so that the integers sum to n_layers * budget exactly, and no layer is left below one row
+ * (a row is taken from the currently largest layer for each layer that would get none).  All-zero
+ * sensitivities give the uniform split.  HOST pointers, pure host computation; budgets_out[l] is
+ * the `budget` to pass to the calls above for layer l. */
+EPICACHE_API int epicache_layer_budgets(const double* sensitivity, int32_t n_layers, double alpha,
+                                        int32_t budget, int32_t* budgets_out);
+
 /* Static, NUL-terminated description of an epicache_status value. */
 EPICACHE_API const char* epicache_status_string(int status);
 

@@ -157,3 +157,40 @@ def evict_step(q, k, v, n_ctx: int, M: int, reduce: int = REDUCE_MAX, scale=None
     kk = compact(k if k_bits is None else k_bits, idx)
     vv = compact(v if v_bits is None else v_bits, idx)
     return s, idx, kk, vv
+
+
+def layer_budgets_real(sensitivity, alpha: float, M: int):
+    """Eq. 6 as printed: M_l = s_l^alpha / sum_j s_j^alpha * (L * M), real valued."""
+    s = np.asarray(sensitivity, dtype=np.float64)
+    w = s ** alpha
+    return w / w.sum() * (len(s) * M)
+
+
+def layer_budgets(sensitivity, alpha: float, M: int):
+    """Integer budgets from Eq. 6 (Alg. 1 phase A2, last line).
+
+    Reading where the paper is silent: round by largest remainder (ties to the lower layer) so the
+    budgets sum to L * M exactly, then make sure no layer has zero rows by moving one row from the
+    currently largest layer; all-zero sensitivities give the uniform split.
+    """
+    L = len(sensitivity)
+    s = [float(x) for x in sensitivity]
+    w = [x ** alpha for x in s]
+    wsum = 0.0
+    for x in w:
+        wsum += x
+    if not wsum > 0.0:
+        return [M] * L
+    quota = [x / wsum * float(L * M) for x in w]
+    out = [int(math.floor(x)) for x in quota]
+    frac = [x - math.floor(x) for x in quota]
+    for _ in range(L * M - sum(out)):
+        best = max(range(L), key=lambda l: (frac[l], -l))
+        out[best] += 1
+        frac[best] = -1.0
+    for l in range(L):
+        if out[l] < 1:
+            big = max(range(L), key=lambda j: (out[j], -j))
+            out[big] -= 1
+            out[l] = 1
+    return out

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "epicache_internal.h"
 
 namespace epicache {
@@ -234,6 +236,50 @@ int epicache_evict_step(const epicache_params* params, const void* q, void* k, v
   if (st != EPICACHE_OK) return st;
   if (launch_topk(pl, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
   if (launch_compact(pl, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
+}
+
+int epicache_layer_budgets(const double* sensitivity, int32_t n_layers, double alpha, int32_t budget,
+                           int32_t* budgets_out) {
+  if (!sensitivity || !budgets_out || n_layers < 1 || budget < 1) return EPICACHE_ERR_INVALID_ARG;
+  if (!(alpha >= 0.0) || isinf(alpha)) return EPICACHE_ERR_INVALID_ARG;
+  if ((int64_t)n_layers * budget > INT32_MAX) return EPICACHE_ERR_UNSUPPORTED;
+  std::vector<double> w(n_layers);
+  double wsum = 0.0;
+  for (int l = 0; l < n_layers; l++) {
+    if (!(sensitivity[l] >= 0.0) || isinf(sensitivity[l])) return EPICACHE_ERR_INVALID_ARG;
+    w[l] = pow(sensitivity[l], alpha);
+    wsum += w[l];
+  }
+  const int64_t total = (int64_t)n_layers * budget;
+  if (!(wsum > 0.0) || isinf(wsum)) {  // nothing to go by: uniform
+    for (int l = 0; l < n_layers; l++) budgets_out[l] = budget;
+    return EPICACHE_OK;
+  }
+  std::vector<double> frac(n_layers);
+  int64_t given = 0;
+  for (int l = 0; l < n_layers; l++) {
+    const double quota = w[l] / wsum * (double)total;  // Eq. 6
+    const double fl = floor(quota);
+    budgets_out[l] = (int32_t)fl;
+    frac[l] = quota - fl;
+    given += budgets_out[l];
+  }
+  for (int64_t left = total - given; left > 0; left--) {  // largest remainder first, ties to the lower layer
+    int best = 0;
+    for (int l = 1; l < n_layers; l++)
+      if (frac[l] > frac[best]) best = l;
+    budgets_out[best] += 1;
+    frac[best] = -1.0;
+  }
+  for (int l = 0; l < n_layers; l++) {  // no layer without a row
+    if (budgets_out[l] >= 1) continue;
+    int big = 0;
+    for (int j = 1; j < n_layers; j++)
+      if (budgets_out[j] > budgets_out[big]) big = j;
+    budgets_out[big] -= 1;
+    budgets_out[l] = 1;
+  }
   return EPICACHE_OK;
 }
 

@@ -338,3 +338,31 @@ def test_block_prefill_sweep_with_resynchronisation():
         cache_k = torch.from_numpy(o_k.view(np.int16)).view(torch.bfloat16)
         cache_v = torch.from_numpy(o_v.view(np.int16)).view(torch.bfloat16)
         assert cache_k.shape[2] == n_keep
+
+
+def test_sweep_with_sensitivity_aware_layer_budgets():
+    """Sec. 3.2: every layer runs the same block sweep under its own budget from Eq. 6 (one call per
+    layer, budgets from epicache_layer_budgets); each layer's cache settles at exactly its budget and the
+    budgets add up to L * M."""
+    w = wl("llama31_8b", E=2, Hq=8, Hkv=2, p=32, M=384, B=256, L=3)
+    budgets = ep.epicache_layer_budgets([0.12, 0.31, 0.05], 2.0, w.M)
+    assert budgets == orc.layer_budgets([0.12, 0.31, 0.05], 2.0, w.M) and sum(budgets) == w.L * w.M
+    say(f"layer budgets {budgets}")
+    for layer, M_l in enumerate(budgets):
+        wl_l = w.scaled(M=M_l)
+        cache_k = cache_v = None
+        for step in range(4):
+            q, bk, bv = synth.make_layer(wl_l, layer=layer, step=step, n_ctx=w.B)
+            k = bk if cache_k is None else torch.cat([cache_k, bk], dim=2)
+            v = bv if cache_v is None else torch.cat([cache_v, bv], dim=2)
+            N = k.shape[2]
+            assert N <= M_l + w.B
+            scores, keep, kd, vd = run_evict_step(wl_l, q, k, v, N, orc.REDUCE_MAX)
+            o_scores, o_keep, o_k, o_v = orc.evict_step(*pu.oracle_inputs(q, k), None, N, M_l, orc.REDUCE_MAX,
+                                                        k_bits=synth.raw_bits_numpy(k), v_bits=synth.raw_bits_numpy(v))
+            pu.assert_scores_close(scores, o_scores, pu.RTOL_BF16, f"layer {layer} step {step}")
+            pu.assert_keep_matches(keep, o_scores, M_l, pu.RTOL_BF16, f"layer {layer} step {step}")
+            cache_k = torch.from_numpy(o_k.view(np.int16)).view(torch.bfloat16)
+            cache_v = torch.from_numpy(o_v.view(np.int16)).view(torch.bfloat16)
+            assert cache_k.shape[2] == min(M_l, N)
+        assert cache_k.shape[2] == M_l
