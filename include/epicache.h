@@ -126,6 +126,13 @@ EPICACHE_API int epicache_evict_step(const epicache_params* params, const void* 
                         float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
+/* epicache_evict_step with the scoring done by epicache_score_lse: for callers whose prefill
+ * attention kernel already returned each patch row's log-sum-exp (row_lse as documented there).
+ * Everything else as epicache_evict_step. */
+EPICACHE_API int epicache_evict_step_lse(const epicache_params* params, const void* q, void* k, void* v,
+                        const float* row_lse, float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
 /* Sec. 3.2, Eq. 6 / Alg. 1 phase A2: split the global budget n_layers * budget over the layers in
  * proportion to sensitivity[l]^alpha (sensitivity[l] = 1 - sigma_l >= 0, alpha >= 0 the sharpness).
  * The paper's allocation is real-valued; here it is rounded by largest remainder (ties to the lower

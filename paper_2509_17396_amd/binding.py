@@ -22,7 +22,7 @@ REDUCE_MAX, REDUCE_SUM = 0, 1
 
 ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
-    "epicache_evict_step", "epicache_layer_budgets", "epicache_status_string", "epicache_version",
+    "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets", "epicache_status_string", "epicache_version",
 )
 
 
@@ -81,9 +81,10 @@ def load() -> ctypes.CDLL:
     lib.epicache_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.epicache_compact.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_layer_budgets.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
-    for name in ENTRY_POINTS[:7]:
+    for name in ENTRY_POINTS[:8]:
         getattr(lib, name).restype = i32
     lib.epicache_status_string.argtypes = [i32]
     lib.epicache_status_string.restype = ctypes.c_char_p
@@ -162,6 +163,12 @@ def epicache_evict_step(params: Params, q, k, v, workspace, scores=None, keep_id
     _check(load().epicache_evict_step(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
                                       _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step")
+
+
+def epicache_evict_step_lse(params: Params, q, k, v, row_lse, workspace, scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step_lse(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(row_lse),
+                                          _ptr(scores), _ptr(keep_idx), _ptr(workspace), workspace.numel(),
+                                          _stream()), "epicache_evict_step_lse")
 
 
 def epicache_layer_budgets(sensitivity, alpha: float, budget: int):

@@ -204,15 +204,15 @@ int epicache_compact(const epicache_params* params, const int32_t* keep_idx, voi
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
-int epicache_evict_step(const epicache_params* params, const void* q, void* k, void* v,
-                        float* scores_opt, int32_t* keep_idx_opt, void* workspace,
-                        size_t workspace_bytes, void* hip_stream) {
+static int evict_step_impl(const epicache_params* params, const void* q, void* k, void* v,
+                           const float* row_lse, bool with_lse, float* scores_opt, int32_t* keep_idx_opt,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   Plan pl;
   int st = make_plan(params, &pl);
   if (st != EPICACHE_OK) return st;
-  if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (!q || !k || !v || !workspace || (with_lse && !row_lse)) return EPICACHE_ERR_INVALID_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) ||
-      misaligned(scores_opt) || misaligned(keep_idx_opt))
+      misaligned(scores_opt) || misaligned(keep_idx_opt) || misaligned(row_lse))
     return EPICACHE_ERR_INVALID_ARG;
   if (k == v) return EPICACHE_ERR_INVALID_ARG;
   const size_t need = !scores_opt ? (!keep_idx_opt ? pl.ws_total : pl.off_keep) :
@@ -222,21 +222,45 @@ int epicache_evict_step(const epicache_params* params, const void* q, void* k, v
   hipStream_t stream = (hipStream_t)hip_stream;
   float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
   int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
+  auto score = [&]() -> int {
+    if (!with_lse) return run_score(pl, q, k, scores, ws, stream);
+    Plan p1 = pl;
+    p1.n_splits = 1;  // the caller's normalisers take the place of pass 1
+    float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
+    if (launch_lse_to_stats(p1, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, true, stream)
+                               : launch_score_generic(p1, q, k, scores, stats, true, stream);
+    return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+  };
 
   if (pl.N <= pl.M) {  // nothing to evict: the cache is still filling up (App. A.3)
     if (scores_opt) {
-      st = run_score(pl, q, k, scores, ws, stream);
+      st = score();
       if (st != EPICACHE_OK) return st;
     }
     if (keep_idx_opt && launch_iota_keep(pl, keep, stream) != hipSuccess)
       return EPICACHE_ERR_DEVICE;
     return EPICACHE_OK;
   }
-  st = run_score(pl, q, k, scores, ws, stream);
+  st = score();
   if (st != EPICACHE_OK) return st;
   if (launch_topk(pl, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
   if (launch_compact(pl, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
   return EPICACHE_OK;
+}
+
+int epicache_evict_step(const epicache_params* params, const void* q, void* k, void* v,
+                        float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  return evict_step_impl(params, q, k, v, nullptr, false, scores_opt, keep_idx_opt, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+int epicache_evict_step_lse(const epicache_params* params, const void* q, void* k, void* v,
+                            const float* row_lse, float* scores_opt, int32_t* keep_idx_opt,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return evict_step_impl(params, q, k, v, row_lse, true, scores_opt, keep_idx_opt, workspace,
+                         workspace_bytes, hip_stream);
 }
 
 int epicache_layer_budgets(const double* sensitivity, int32_t n_layers, double alpha, int32_t budget,

@@ -366,3 +366,30 @@ def test_sweep_with_sensitivity_aware_layer_budgets():
             cache_v = torch.from_numpy(o_v.view(np.int16)).view(torch.bfloat16)
             assert cache_k.shape[2] == min(M_l, N)
         assert cache_k.shape[2] == M_l
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_evict_step_lse_equals_evict_step_up_to_the_band(reduce):
+    """The step with caller-supplied row normalisers against the oracle's whole step."""
+    import scipy.special
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=64, M=700, B=500)
+    N = w.N
+    say(f"evict_step_lse reduce={reduce}")
+    q, k, v = synth.make_layer(w, layer=4)
+    qq, kk = pu.oracle_inputs(q, k)
+    z = np.einsum("bhtd,bhnd->bhtn", qq, np.repeat(kk, w.G, axis=1)) / w.d ** 0.5
+    lse32 = scipy.special.logsumexp(z, axis=3).astype(np.float32)
+    qd, kd, vd = q.to(DEV), k.to(DEV).clone(), v.to(DEV).clone()
+    prm = ep.make_params(qd, kd, n_cached=w.M, n_block=w.B, budget=w.M, reduce=reduce)
+    ws = ep.alloc_workspace(prm)
+    scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+    keep = torch.full((w.E, w.Hkv, w.M), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step_lse(prm, qd, kd, vd, torch.from_numpy(lse32).to(DEV), ws, scores, keep)
+    torch.cuda.synchronize()
+    kb, vb = synth.raw_bits_numpy(k), synth.raw_bits_numpy(v)
+    o_scores, o_keep, o_k, o_v = orc.evict_step(qq, kk, None, N, w.M, reduce, k_bits=kb, v_bits=vb)
+    pu.assert_scores_close(scores.cpu().numpy(), o_scores, pu.RTOL_BF16, "evict_step_lse")
+    keep_np = keep.cpu().numpy()
+    pu.assert_keep_matches(keep_np, o_scores, w.M, pu.RTOL_BF16, "evict_step_lse")
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd.cpu())[:, :, :w.M], orc.compact(kb, keep_np))
+    np.testing.assert_array_equal(synth.raw_bits_numpy(vd.cpu())[:, :, :w.M], orc.compact(vb, keep_np))
