@@ -66,6 +66,7 @@ int make_plan(const epicache_params* prm, Plan* out) {
   for (int i = 0; i < 6; i++)
     if (strides[i] < 0 || strides[i] % 8 != 0) return EPICACHE_ERR_INVALID_ARG;
   if (pl.qst < pl.d || pl.kst < pl.d) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.qst > (1 << 20) || pl.kst > (1 << 20)) return EPICACHE_ERR_UNSUPPORTED;  // 32-bit row offsets in the kernels
   if (pl.qsh < pl.qst * (int64_t)(pl.p - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
   if (pl.ksh < pl.kst * (N64 - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
   if (pl.nb > 1 && (pl.qsb < pl.qsh * (int64_t)(pl.Hq - 1) + pl.qst * (int64_t)(pl.p - 1) + pl.d ||

@@ -63,6 +63,7 @@ def test_workspace_size_is_host_only_and_monotone():
     ("kv_stride_t", 132, ep.ERR_INVALID_ARG),    # not a multiple of 8
     ("kv_stride_h", 1000, ep.ERR_INVALID_ARG),   # capacity below N
     ("head_dim", 12, ep.ERR_UNSUPPORTED),
+    ("kv_stride_t", 1 << 21, ep.ERR_UNSUPPORTED),  # token stride beyond the 32-bit row offsets of the kernels
     ("n_cached", (1 << 24) + 8, ep.ERR_INVALID_ARG),  # exceeds the capacity the strides imply
 ])
 def test_bad_params_are_rejected_before_any_launch(field, value, status):

@@ -51,6 +51,15 @@ SCORE_CASES = [
     ("bf16_mfma_student_t", "stress", dict(E=1, Hq=8, Hkv=2, p=64), 2048 + 13, None),
     ("bf16_mfma_topics_G7", "qwen25_7b", dict(E=2, Hq=14, Hkv=2, p=32), 1536, None),
     ("bf16_generic_d96", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=9, d=96), 150, None),
+    ("bf16_mfma_one_key", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=5), 1, 1),
+    ("bf16_mfma_exactly_one_tile", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=40), 64, 64),
+    ("bf16_mfma_one_tile_plus_one", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=40), 65, 65),
+    ("bf16_mfma_R32", "llama32_3b", dict(E=1, Hq=2, Hkv=2, p=32), 500, None),
+    ("bf16_mfma_R64", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=32), 500, None),
+    ("bf16_mfma_R128", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=64), 500, None),
+    ("bf16_mfma_R256", "llama32_3b", dict(E=1, Hq=8, Hkv=2, p=64), 700, None),
+    ("bf16_mfma_d64_R300", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=100, d=64), 450, None),
+    ("bf16_mfma_huge_logits", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=16), 300, None),
 ]
 
 
@@ -62,6 +71,8 @@ def test_score_matches_oracle(case, reduce):
     N = w.N if n_ctx is None else n_ctx
     say(f"score {name} reduce={reduce} N={N} R={w.R} d={w.d} {w.dtype}")
     q, k, _ = synth.make_layer(w, layer=0, n_ctx=N, capacity=cap)
+    if name.endswith("huge_logits"):   # logits in the hundreds: every row is one-hot, weights underflow
+        q = (q.float() * 40).to(q.dtype)
     got = gpu_score(q.to(DEV), k.to(DEV), N, w.M, reduce)
     qq, kk = pu.oracle_inputs(q, k)
     want = orc.score(qq, kk, N, reduce)
