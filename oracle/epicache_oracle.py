@@ -194,3 +194,114 @@ def layer_budgets(sensitivity, alpha: float, M: int):
             out[big] -= 1
             out[l] = 1
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Ragged batches: every (batch item, KV head) has its own number of context rows and every
+# batch item its own budget.  Needed for head-wise non-uniform retention (App. A.2, last
+# paragraph: every method of the paper's experiments selects tokens head-wise non-uniformly in
+# the manner of Ada-KV) and for layers with different budgets (Eq. 6) folded into one batch.
+#
+# Reading (the paper only cites the rule, it does not print it): the scores of the Hkv heads of
+# one batch item (one layer of one episode) form one pool; the Hkv * M highest-scoring entries
+# of the pool are kept, so a head whose attention is spread over many tokens keeps more rows
+# than a head that concentrates on a few, and the layer as a whole still holds Hkv * M rows.
+# Ties go to the lower head, then to the lower token index.  No per-head floor is applied.
+# Which variant of the cited rule the authors ran cannot be checked: parity unpinned for that
+# choice; the pooled top-k itself is pinned by its counting definition.
+# ---------------------------------------------------------------------------------------------
+
+def score_ragged(q, k, n_ctx, reduce: int = REDUCE_MAX, scale: float | None = None):
+    """Eq. 1 per (b, h) over the first n_ctx[b][h] rows of k[b, h].
+
+    Returns rows[b][h]: float64 array of length n_ctx[b][h] (empty where it is 0).
+    """
+    nb, Hq, p, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    rows = []
+    for b in range(nb):
+        per_head = []
+        for h in range(Hkv):
+            n = int(n_ctx[b][h])
+            if n == 0:
+                per_head.append(np.empty(0, dtype=np.float64))
+                continue
+            qr = np.asarray(q[b, h * G:(h + 1) * G], dtype=np.float64).reshape(G * p, d)
+            keys = np.asarray(k[b, h, :n], dtype=np.float64)
+            attn = attention_weights(qr, keys, scale)
+            per_head.append(attn.max(axis=0) if reduce == REDUCE_MAX else attn.sum(axis=0))
+        rows.append(per_head)
+    return rows
+
+
+def select_pooled(head_scores, M: int):
+    """Head-wise non-uniform retention for one batch item.
+
+    head_scores: list of Hkv 1-D arrays (lengths may differ).  Keeps the min(Hkv * M, total)
+    largest entries of the concatenation; ties -> lower head, then lower index.
+    Returns a list of Hkv ascending int32 index arrays.
+    """
+    H = len(head_scores)
+    lens = [len(s) for s in head_scores]
+    pool = np.concatenate([np.asarray(s) for s in head_scores]) if H else np.empty(0)
+    total = pool.shape[0]
+    n_keep = min(H * M, total)
+    order = np.lexsort((np.arange(total), -pool))[:n_keep]   # score descending, then pool position
+    kept = np.zeros(total, dtype=bool)
+    kept[order] = True
+    out, start = [], 0
+    for h in range(H):
+        out.append(np.nonzero(kept[start:start + lens[h]])[0].astype(np.int32))
+        start += lens[h]
+    return out
+
+
+def select_pooled_by_counting(head_scores, M: int):
+    """The same sets from the counting definition, O(total^2), pure Python, tiny inputs only.
+
+    Entry (h, i) is kept iff fewer than Hkv * M entries beat it, where (g, j) beats (h, i) when it
+    scores higher, or equally with (g, j) < (h, i) in lexicographic order.
+    """
+    H = len(head_scores)
+    flat = [(float(s), h, i) for h in range(H) for i, s in enumerate(head_scores[h])]
+    out = [[] for _ in range(H)]
+    for (s, h, i) in flat:
+        beaten_by = 0
+        for (t, g, j) in flat:
+            if t > s or (t == s and (g, j) < (h, i)):
+                beaten_by += 1
+        if beaten_by < H * M:
+            out[h].append(i)
+    return out
+
+
+def select_ragged(rows, budgets, pooled: bool):
+    """rows[b][h]: 1-D scores; budgets[b]: M_b.  Returns keep[b][h]: ascending int32 arrays."""
+    keep = []
+    for b, per_head in enumerate(rows):
+        M = int(budgets[b])
+        if pooled:
+            keep.append(select_pooled(per_head, M))
+        else:
+            keep.append([topk_1d(np.asarray(s), M) for s in per_head])
+    return keep
+
+
+def evict_step_ragged(q, k, v, n_ctx, budgets, pooled: bool, reduce: int = REDUCE_MAX, scale=None,
+                      k_bits=None, v_bits=None):
+    """One eviction step on a ragged batch: score, select (per head or pooled), compact.
+
+    As in evict_step the selection reads the scores rounded to float32.
+    Returns (rows, keep, K', V') with K'[b][h] = the kept rows of k[b, h] (or of k_bits), in order.
+    """
+    rows = score_ragged(q, k, n_ctx, reduce, scale)
+    rows32 = [[s.astype(np.float32) for s in per_head] for per_head in rows]
+    keep = select_ragged(rows32, budgets, pooled)
+    ks = k if k_bits is None else k_bits
+    vs = v if v_bits is None else v_bits
+    kk = [[ks[b, h][idx] for h, idx in enumerate(per_head)] for b, per_head in enumerate(keep)]
+    vv = [[vs[b, h][idx] for h, idx in enumerate(per_head)] for b, per_head in enumerate(keep)]
+    return rows, keep, kk, vv
