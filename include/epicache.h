@@ -134,6 +134,62 @@ EPICACHE_API int epicache_evict_step_lse(const epicache_params* params, const vo
                         const float* row_lse, float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Ragged batches: every (batch item, KV head) has its own number of context rows and every batch
+ * item its own budget, both read from DEVICE memory, so a sequence of steps needs no host
+ * round trip.  Two uses: layers with different budgets (Sec. 3.2, Eq. 6) folded into one launch,
+ * and head-wise non-uniform retention (App. A.2, last paragraph: every method in the paper's
+ * experiments selects tokens head-wise non-uniformly in the manner of Ada-KV), after which the
+ * heads of one layer hold different numbers of rows.
+ *
+ * In these calls params->n_cached + params->n_block = N_max bounds every context length (it sizes
+ * the strides of `scores`, the launch grids and the capacity check) and params->budget bounds
+ * every per-item budget.
+ *   n_ctx   [n_batch, n_kv_heads] int32: context rows of (b, h); values are clamped to 0..N_max
+ *   budgets [n_batch] int32: M_b, clamped to 1..params->budget; NULL = params->budget everywhere
+ *   scores  [n_batch, n_kv_heads, N_max] float32: entries at or beyond n_ctx[b,h] are not written
+ *   keep    [n_batch, n_kv_heads, keep_capacity] int32: the first n_kept[b,h] entries are valid
+ *   n_kept  [n_batch, n_kv_heads] int32 (out): rows (b, h) holds after the step
+ * keep_capacity = min(budget, N_max) for EPICACHE_SELECT_PER_HEAD and
+ * min(n_kv_heads * budget, N_max) for EPICACHE_SELECT_POOLED.
+ * Pooled selection additionally needs n_kv_heads <= 1024 and n_kv_heads * N_max < 2^31. */
+typedef enum {
+  EPICACHE_SELECT_PER_HEAD = 0, /* each (b, h) keeps its min(M_b, n_ctx) best rows (Sec. 3.1 Stage 2)   */
+  EPICACHE_SELECT_POOLED = 1    /* the heads of item b share one pool: its min(Hkv * M_b, sum of n_ctx)  */
+                                /* best entries are kept; ties: lower head, then lower row (App. A.2)    */
+} epicache_select;
+
+/* Workspace bytes for the ragged calls below and the row pitch of `keep`.  Pure host computation. */
+EPICACHE_API int epicache_ragged_workspace_size(const epicache_params* params, int32_t select,
+                                                size_t* bytes_out, int32_t* keep_capacity_out);
+
+/* Eq. 1 as epicache_score, over the first n_ctx[b,h] rows of K[b,h].  Rows with n_ctx = 0 get no
+ * scores. */
+EPICACHE_API int epicache_score_ragged(const epicache_params* params, const void* q, const void* k,
+                                       const int32_t* n_ctx, float* scores, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream);
+
+/* Retention on given scores.  Writes keep (ascending within each head) and n_kept.  Score order and
+ * per-head tie rule as epicache_topk. */
+EPICACHE_API int epicache_select_ragged(const epicache_params* params, int32_t select, const float* scores,
+                                        const int32_t* n_ctx, const int32_t* budgets, int32_t* keep_idx,
+                                        int32_t* n_kept, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream);
+
+/* In-place compaction as epicache_compact with n_kept[b,h] rows per head; `select` only fixes the
+ * row pitch of keep_idx. */
+EPICACHE_API int epicache_compact_ragged(const epicache_params* params, int32_t select,
+                                         const int32_t* keep_idx, const int32_t* n_kept, void* k, void* v,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* score_ragged -> select_ragged -> compact_ragged on one stream.  n_kept is required: it is the
+ * n_cached of each head for the next step (n_ctx_next = n_kept + next block).  scores_opt and
+ * keep_idx_opt may be NULL. */
+EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32_t select, const void* q,
+                                            void* k, void* v, const int32_t* n_ctx, const int32_t* budgets,
+                                            int32_t* n_kept, float* scores_opt, int32_t* keep_idx_opt,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Sec. 3.2, Eq. 6 / Alg. 1 phase A2: split the global budget n_layers * budget over the layers in
  * proportion to sensitivity[l]^alpha (sensitivity[l] = 1 - sigma_l >= 0, alpha >= 0 the sharpness).
  * The paper's allocation is real-valued; here it is rounded by largest remainder (ties to the lower

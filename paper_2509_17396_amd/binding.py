@@ -19,11 +19,15 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "lib
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_DEVICE = range(5)
 DTYPE_F32, DTYPE_BF16 = 0, 1
 REDUCE_MAX, REDUCE_SUM = 0, 1
+SELECT_PER_HEAD, SELECT_POOLED = 0, 1
 
 ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
-    "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets", "epicache_status_string", "epicache_version",
+    "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets",
+    "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
+    "epicache_evict_step_ragged", "epicache_status_string", "epicache_version",
 )
+_INT_RETURNING = ENTRY_POINTS[:-2]
 
 
 class Params(ctypes.Structure):
@@ -84,7 +88,13 @@ def load() -> ctypes.CDLL:
     lib.epicache_evict_step_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_layer_budgets.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
-    for name in ENTRY_POINTS[:8]:
+    i32c = ctypes.c_int32
+    lib.epicache_ragged_workspace_size.argtypes = [pp, i32c, ctypes.POINTER(sz), ctypes.POINTER(i32c)]
+    lib.epicache_score_ragged.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_select_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in _INT_RETURNING:
         getattr(lib, name).restype = i32
     lib.epicache_status_string.argtypes = [i32]
     lib.epicache_status_string.restype = ctypes.c_char_p
@@ -169,6 +179,46 @@ def epicache_evict_step_lse(params: Params, q, k, v, row_lse, workspace, scores=
     _check(load().epicache_evict_step_lse(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(row_lse),
                                           _ptr(scores), _ptr(keep_idx), _ptr(workspace), workspace.numel(),
                                           _stream()), "epicache_evict_step_lse")
+
+
+def epicache_ragged_workspace_size(params: Params, select: int):
+    """-> (workspace bytes, keep_capacity)"""
+    out, cap = ctypes.c_size_t(0), ctypes.c_int32(0)
+    _check(load().epicache_ragged_workspace_size(ctypes.byref(params), int(select), ctypes.byref(out),
+                                                 ctypes.byref(cap)), "epicache_ragged_workspace_size")
+    return out.value, cap.value
+
+
+def alloc_ragged_workspace(params: Params, select: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(epicache_ragged_workspace_size(params, select)[0], 256), dtype=torch.uint8,
+                       device=device)
+
+
+def epicache_score_ragged(params: Params, q, k, n_ctx, scores, workspace) -> None:
+    _check(load().epicache_score_ragged(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(n_ctx), _ptr(scores),
+                                        _ptr(workspace), workspace.numel(), _stream()), "epicache_score_ragged")
+
+
+def epicache_select_ragged(params: Params, select: int, scores, n_ctx, budgets, keep_idx, n_kept,
+                           workspace) -> None:
+    _check(load().epicache_select_ragged(ctypes.byref(params), int(select), _ptr(scores), _ptr(n_ctx),
+                                         _ptr(budgets), _ptr(keep_idx), _ptr(n_kept), _ptr(workspace),
+                                         workspace.numel(), _stream()), "epicache_select_ragged")
+
+
+def epicache_compact_ragged(params: Params, select: int, keep_idx, n_kept, k, v, workspace=None) -> None:
+    _check(load().epicache_compact_ragged(ctypes.byref(params), int(select), _ptr(keep_idx), _ptr(n_kept),
+                                          _ptr(k), _ptr(v), _ptr(workspace),
+                                          0 if workspace is None else workspace.numel(), _stream()),
+           "epicache_compact_ragged")
+
+
+def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budgets, n_kept, workspace,
+                               scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step_ragged(ctypes.byref(params), int(select), _ptr(q), _ptr(k), _ptr(v),
+                                             _ptr(n_ctx), _ptr(budgets), _ptr(n_kept), _ptr(scores),
+                                             _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
+           "epicache_evict_step_ragged")
 
 
 def epicache_layer_budgets(sensitivity, alpha: float, budget: int):

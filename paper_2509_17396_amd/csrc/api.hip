@@ -118,6 +118,31 @@ int make_plan(const epicache_params* prm, Plan* out) {
   pl.off_keep = off;
   off += align256((size_t)nbh * pl.n_keep * sizeof(int32_t));
   pl.ws_total = off;
+  pl.keep_stride = pl.n_keep;
+  *out = pl;
+  return EPICACHE_OK;
+}
+
+// Plan of a ragged call: N and M are the upper bounds, the keep rows are pitched for the selection
+// rule, and the workspace gains the per-head threshold records.
+static int make_ragged_plan(const epicache_params* prm, int32_t select, Plan* out) {
+  Plan pl;
+  int st = make_plan(prm, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (select != EPICACHE_SELECT_PER_HEAD && select != EPICACHE_SELECT_POOLED) return EPICACHE_ERR_INVALID_ARG;
+  const int64_t nbh = (int64_t)pl.nb * pl.Hkv;
+  if (select == EPICACHE_SELECT_POOLED) {
+    if (pl.Hkv > 1024 || (int64_t)pl.Hkv * pl.N >= (int64_t(1) << 31)) return EPICACHE_ERR_UNSUPPORTED;
+    const int64_t pooled = (int64_t)pl.Hkv * pl.M;
+    pl.keep_stride = (int)(pooled < pl.N ? pooled : pl.N);
+  } else {
+    pl.keep_stride = pl.n_keep;
+  }
+  size_t off = pl.off_keep;
+  off += align256((size_t)nbh * pl.keep_stride * sizeof(int32_t));
+  pl.off_select = off;
+  off += align256(select_ragged_record_bytes(pl));
+  pl.ws_total = off;
   *out = pl;
   return EPICACHE_OK;
 }
@@ -262,6 +287,90 @@ int epicache_evict_step_lse(const epicache_params* params, const void* q, void* 
                             void* workspace, size_t workspace_bytes, void* hip_stream) {
   return evict_step_impl(params, q, k, v, row_lse, true, scores_opt, keep_idx_opt, workspace,
                          workspace_bytes, hip_stream);
+}
+
+int epicache_ragged_workspace_size(const epicache_params* params, int32_t select, size_t* bytes_out,
+                                   int32_t* keep_capacity_out) {
+  if (!bytes_out || !keep_capacity_out) return EPICACHE_ERR_INVALID_ARG;
+  Plan pl;
+  int st = make_ragged_plan(params, select, &pl);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = pl.ws_total;
+  *keep_capacity_out = pl.keep_stride;
+  return EPICACHE_OK;
+}
+
+int epicache_score_ragged(const epicache_params* params, const void* q, const void* k, const int32_t* n_ctx,
+                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !n_ctx || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(n_ctx) || misaligned(scores) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  pl.n_ctx = n_ctx;
+  return run_score(pl, q, k, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
+}
+
+int epicache_select_ragged(const epicache_params* params, int32_t select, const float* scores,
+                           const int32_t* n_ctx, const int32_t* budgets, int32_t* keep_idx, int32_t* n_kept,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_ragged_plan(params, select, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!scores || !n_ctx || !keep_idx || !n_kept || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(scores) || misaligned(n_ctx) || misaligned(budgets) || misaligned(keep_idx) ||
+      misaligned(n_kept) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < pl.ws_total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  pl.n_ctx = n_ctx;
+  hipError_t e = launch_select_ragged(pl, select, scores, budgets, keep_idx, n_kept,
+                                      static_cast<char*>(workspace) + pl.off_select, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_compact_ragged(const epicache_params* params, int32_t select, const int32_t* keep_idx,
+                            const int32_t* n_kept, void* k, void* v, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;  // in-place gather, no staging buffer
+  Plan pl;
+  int st = make_ragged_plan(params, select, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!keep_idx || !n_kept || !k || !v) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(keep_idx) || misaligned(n_kept) || misaligned(k) || misaligned(v)) return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  pl.n_kept = n_kept;
+  hipError_t e = launch_compact(pl, keep_idx, k, v, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_evict_step_ragged(const epicache_params* params, int32_t select, const void* q, void* k, void* v,
+                               const int32_t* n_ctx, const int32_t* budgets, int32_t* n_kept,
+                               float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_ragged_plan(params, select, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !n_ctx || !n_kept || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(n_ctx) || misaligned(budgets) ||
+      misaligned(n_kept) || misaligned(scores_opt) || misaligned(keep_idx_opt) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < pl.ws_total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
+  int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
+  pl.n_ctx = n_ctx;
+  st = run_score(pl, q, k, scores, ws, stream);
+  if (st != EPICACHE_OK) return st;
+  if (launch_select_ragged(pl, select, scores, budgets, keep, n_kept, ws + pl.off_select, stream) != hipSuccess)
+    return EPICACHE_ERR_DEVICE;
+  pl.n_kept = n_kept;
+  if (launch_compact(pl, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
 }
 
 int epicache_layer_budgets(const double* sensitivity, int32_t n_layers, double alpha, int32_t budget,

@@ -41,8 +41,12 @@ __global__ __launch_bounds__(256) void compact_rows(unsigned char* __restrict__ 
   const size_t pitch = (size_t)pl.kst * pl.elem;
   unsigned char* base = (tensor ? vbuf : kbuf) + ((size_t)b * pl.ksb + (size_t)h * pl.ksh) * pl.elem +
                         ((size_t)slice * tpr + col) * 16;
-  const int32_t* idx = keep + (size_t)bh * pl.n_keep;
-  const int n = pl.n_keep;
+  const int32_t* idx = keep + (size_t)bh * pl.keep_stride;
+  int n = pl.n_keep;
+  if (pl.n_kept) {  // ragged batch: this head's own count, never beyond the pitch of its index row
+    n = pl.n_kept[bh];
+    n = n < 0 ? 0 : (n > pl.keep_stride ? pl.keep_stride : n);
+  }
   const int chunk = kUnroll * rpr;
 
   int src[kUnroll];
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(256) void compact_rows(unsigned char* __restrict__ 
 
 hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
                           hipStream_t stream) {
-  if (pl.N <= pl.M) return hipSuccess;  // nothing is evicted, rows stay where they are
+  if (!pl.n_kept && pl.N <= pl.M) return hipSuccess;  // nothing is evicted, rows stay where they are
   const int row_chunks = pl.d * pl.elem / 16;  // 16-byte chunks per row (head_dim % 8 == 0)
   const int64_t problems = (int64_t)pl.nb * pl.Hkv * 2;
   int slices = 1;

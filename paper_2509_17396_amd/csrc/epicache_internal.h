@@ -31,7 +31,19 @@ struct Plan {
   int reduce_tiles_per_split;
   // workspace layout (byte offsets, 256-aligned)
   size_t off_stats, off_scores, off_keep, ws_total;
+  // ragged batches: device arrays indexed by b * Hkv + h, null in the uniform calls
+  const int32_t* n_ctx;   // context rows per (b, h), at most N; N is then the pitch of a score row
+  const int32_t* n_kept;  // rows kept per (b, h), read by the compaction
+  int keep_stride;        // pitch of a row of kept indices (n_keep in the uniform calls)
+  size_t off_select;      // per-(b, h) threshold records of the ragged selection
 };
+
+// Context rows of (b, h): the per-head length of a ragged batch, clamped to what the strides were checked for.
+__device__ __forceinline__ int ctx_rows(const Plan& pl, int bh) {
+  if (!pl.n_ctx) return pl.N;
+  const int n = pl.n_ctx[bh];
+  return n < 0 ? 0 : (n > pl.N ? pl.N : n);
+}
 
 constexpr int kKeyTile = 64;     // keys staged per LDS tile in the statistics pass
 constexpr int kKeysPerWG = 256;  // keys per workgroup in the reduction pass
@@ -49,5 +61,9 @@ hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipSt
 hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);
 hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
                           hipStream_t stream);
+size_t select_ragged_record_bytes(const Plan& pl);
+// Ragged selection: per-(b, h) (select == per head) or per-b pooled thresholds, then the kept indices.
+hipError_t launch_select_ragged(const Plan& pl, int select, const float* scores, const int32_t* budgets,
+                                int32_t* keep, int32_t* n_kept, void* records, hipStream_t stream);
 
 }  // namespace epicache

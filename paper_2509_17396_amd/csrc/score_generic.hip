@@ -33,8 +33,9 @@ __global__ __launch_bounds__(256) void score_generic_stats(const T* __restrict__
   __syncthreads();
   if (!active) return;
   const T* kbase = k + b * pl.ksb + (int64_t)h * pl.ksh;
+  const int N = ctx_rows(pl, bh);
   float m = -INFINITY, D = 0.f;
-  for (int i = lane; i < pl.N; i += 64) {
+  for (int i = lane; i < N; i += 64) {
     const T* krow = kbase + (int64_t)i * pl.kst;
     float dot = 0.f;
     for (int c = 0; c < pl.d; c++) dot = fmaf(qs[wave][c], to_f32(krow[c]), dot);
@@ -66,11 +67,13 @@ __global__ __launch_bounds__(256) void score_generic_reduce(const T* __restrict_
   float* red = smem + 32 * ldk;    // [8][32]
   const int bh = blockIdx.y, b = bh / pl.Hkv, h = bh % pl.Hkv;
   const int key0 = blockIdx.x * 32;
+  const int N = ctx_rows(pl, bh);
+  if (key0 >= N) return;  // a shorter head of a ragged batch: no keys here
   const T* kbase = k + b * pl.ksb + (int64_t)h * pl.ksh;
   for (int e = threadIdx.x; e < 32 * pl.d; e += 256) {
     const int kk = e / pl.d, c = e % pl.d;
     const int i = key0 + kk;
-    ks[kk * ldk + c] = i < pl.N ? to_f32(kbase[(int64_t)i * pl.kst + c]) : 0.f;
+    ks[kk * ldk + c] = i < N ? to_f32(kbase[(int64_t)i * pl.kst + c]) : 0.f;
   }
   __syncthreads();
   const int key = threadIdx.x & 31, rl = threadIdx.x >> 5;
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(256) void score_generic_reduce(const T* __restrict_
   }
   red[rl * 32 + key] = acc;
   __syncthreads();
-  if (rl == 0 && key0 + key < pl.N) {
+  if (rl == 0 && key0 + key < N) {
     for (int j = 1; j < 8; j++) {
       const float o = red[j * 32 + key];
       acc = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(acc, o) : acc + o;

@@ -292,11 +292,20 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   const bool active = row0 < pl.R;  // waves without rows only help staging the key tiles
   const float c2 = pl.c2;
 
-  const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
+  const int N = ctx_rows(pl, bh);
+  const int tiles = (N + kKeyTile - 1) / kKeyTile;
   const int t_begin = split * pl.tiles_per_split;
+  if (t_begin >= tiles) {
+    // a head shorter than the batch's longest: this split holds none of its keys and contributes
+    // an empty sum under a maximum below every logit
+    const int r_end = min(pl.R, (rb + 1) * (32 * NQ * NW));
+    for (int r = rb * (32 * NQ * NW) + tid; r < r_end; r += NW * 64)
+      stats[((size_t)bh * pl.n_splits + split) * pl.Rpad + r] = make_float2(kMasked, 0.f);
+    return;
+  }
   const int t_end = min(tiles, t_begin + pl.tiles_per_split);
   // a ragged last tile (N % 64 != 0) is handled after the pipelined loop over full tiles
-  const int t_full = (t_end == tiles && pl.N % kKeyTile != 0) ? t_end - 1 : t_end;
+  const int t_full = (t_end == tiles && N % kKeyTile != 0) ? t_end - 1 : t_end;
 
   // query fragments stay in registers for the whole key loop
   bf16x8 qf[NQ][KS];
@@ -359,7 +368,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   if (t_full < t_end) {
     // ragged last tile: rows beyond N re-read the last key and are masked out of the statistics
     const int t = t_full;
-    const int nrows = pl.N - t * kKeyTile;  // 1..63
+    const int nrows = N - t * kKeyTile;  // 1..63
     const unsigned char* tile = kbase + (size_t)t * kKeyTile * kstride;
     __syncthreads();  // every wave is done reading both buffers
     ST::run_rows(lds0, wave, lane, [=](int row) { return tile + (size_t)min(row, nrows - 1) * kstride; });
@@ -490,6 +499,8 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
   const int bh = blockIdx.y, b = bh / pl.Hkv, h = bh % pl.Hkv;
+  const int N = ctx_rows(pl, bh);
+  if ((int)blockIdx.x * kKeysPerWG >= N) return;  // a shorter head of a ragged batch: no keys here
   const int key0 = blockIdx.x * kKeysPerWG + wave * 64;
   const float c2 = pl.c2;
 
@@ -538,7 +549,7 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   bf16x8 kf[2][KS];
 #pragma unroll
   for (int s = 0; s < 2; s++) {
-    const int key = min(key0 + s * 32 + l32, pl.N - 1);
+    const int key = min(key0 + s * 32 + l32, N - 1);
     const bf16_t* krow = kbase + (int64_t)key * pl.kst + hi * 8;
 #pragma unroll
     for (int j = 0; j < KS; j++)
@@ -594,7 +605,7 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
     if (REDUCE == EPICACHE_REDUCE_MAX) val = ex2(fmaxf(col[s], o));
     else val = col[s] + o;
     const int key = key0 + s * 32 + l32;
-    if (hi == 0 && key < pl.N) scores[(size_t)bh * pl.N + key] = val;
+    if (hi == 0 && key < N) scores[(size_t)bh * pl.N + key] = val;
   }
 }
 
@@ -633,9 +644,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   const bool active = row0 < pl.R;
   const float c2 = pl.c2;
 
-  const int tiles = (pl.N + kKeyTile - 1) / kKeyTile;
+  const int N = ctx_rows(pl, bh);
+  const int tiles = (N + kKeyTile - 1) / kKeyTile;
   const int t_begin = split * pl.reduce_tiles_per_split;
   const int t_end = min(tiles, t_begin + pl.reduce_tiles_per_split);
+  if (t_begin >= t_end) return;  // a shorter head of a ragged batch: no keys in this split
 
   const unsigned char* kbase = reinterpret_cast<const unsigned char*>(k + b * pl.ksb + (int64_t)h * pl.ksh);
   const uint32_t kstride = (uint32_t)pl.kst * 2;
@@ -644,12 +657,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   const uint32_t lds0 = lds_address(lds);
   auto stage_keys = [&](uint32_t dst, int t) {
     const unsigned char* tile = kbase + (size_t)t * kKeyTile * kstride;
-    const int nrows = pl.N - t * kKeyTile;
+    const int nrows = N - t * kKeyTile;
     if (nrows >= kKeyTile) ST::run(dst, tile, koff, wave);
     else  // ragged last tile: rows beyond N re-read the last key; their results are never written
       ST::run_rows(dst, wave, lane, [=](int row) { return tile + (size_t)min(row, nrows - 1) * kstride; });
   };
-  if (t_begin < t_end) stage_keys(lds0, t_begin);
+  stage_keys(lds0, t_begin);
 
   // combine the key splits of pass 1 into minus one base-2 log-sum-exp per query row
   for (int r = tid; r < kRows; r += NW * 64) {
@@ -726,7 +739,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
     __syncthreads();  // tile t+1 staged, part[t & 1] complete; it is rewritten two barriers from now
     if (tid < 64) {
       const int key = t * kKeyTile + tid;
-      if (key < pl.N) {
+      if (key < N) {
         float v = part[t & 1][0][tid];
 #pragma unroll
         for (int w = 1; w < NW; w++)

@@ -9,19 +9,10 @@
 // plus the first `need_eq` keys equal to it (lower index wins a tie), which
 // makes the count exactly n_keep and keeps the output ascending.
 #include "epicache_internal.h"
+#include "select_util.h"
 
 namespace epicache {
 namespace {
-
-__device__ __forceinline__ uint32_t order_key(float x) {
-  const uint32_t u = __float_as_uint(x);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ int lanes_below(uint64_t mask) {
-  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                   __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
-}
 
 // VPT > 0: each thread keeps VPT keys in registers (N <= blockDim.x * VPT).
 // VPT == 0: keys are re-read from global memory in every pass (any N).
@@ -73,35 +64,8 @@ __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ sc
       }
     }
     __syncthreads();
-    // every wave scans the 256 bins from the top; lane l owns bins 255-4l .. 252-4l
-    uint32_t c[4];
-#pragma unroll
-    for (int x = 0; x < 4; x++) c[x] = hist[pass][255 - 4 * lane - x];
-    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-    uint32_t incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
-    uint32_t excl = incl - mine;
-    const bool here = excl < kth && kth <= incl;  // true in exactly one lane
-    uint32_t bin = 0, above = 0;
-    if (here) {
-      uint32_t run = excl;
-#pragma unroll
-      for (int x = 0; x < 4; x++) {
-        if (run < kth && kth <= run + c[x]) {
-          bin = 255 - 4 * lane - x;
-          above = run;
-        }
-        run += c[x];
-      }
-    }
-    const uint64_t who = __ballot(here);
-    const int src = __ffsll((unsigned long long)who) - 1;
-    bin = __shfl(bin, src);
-    above = __shfl(above, src);
+    uint32_t bin, above;
+    locate_digit(hist[pass], kth, lane, bin, above);  // every wave scans the 256 bins itself
     prefix |= bin << shift;
     mask |= 255u << shift;
     kth -= above;

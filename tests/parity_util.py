@@ -75,3 +75,42 @@ def oracle_score_one_head(q: torch.Tensor, k: torch.Tensor, b: int, h: int, N: i
     qq = synth.to_f64_numpy(q[b:b + 1, h * G:(h + 1) * G])
     kk = synth.to_f64_numpy(k[b:b + 1, h:h + 1, :N])
     return orc.score(qq, kk, N, reduce, scale)[0, 0]
+
+
+def assert_ragged_keep_matches(gpu_keep, oracle_rows, budgets, pooled: bool, rtol: float, what=""):
+    """Ragged counterpart of assert_keep_matches.  gpu_keep[b][h]: kept indices of head (b, h);
+    oracle_rows[b][h]: float64 oracle scores of its n_ctx rows.  Counts are exact (per head, or per
+    item when pooled); membership may differ from the oracle's only for tokens whose oracle score lies
+    within the score tolerance of the oracle's threshold score.  Returns #tokens that differ."""
+    differ = 0
+    for b, rows in enumerate(oracle_rows):
+        H, M = len(rows), int(budgets[b])
+        rows32 = [r.astype(np.float32) for r in rows]
+        ref = orc.select_pooled(rows32, M) if pooled else [orc.topk_1d(r, M) for r in rows32]
+        for h in range(H):
+            got = np.asarray(gpu_keep[b][h])
+            assert (got >= 0).all() and (got < len(rows[h])).all(), f"{what} b={b} h={h}: index out of range"
+            assert (np.diff(got) > 0).all(), f"{what} b={b} h={h}: indices not strictly ascending"
+            if not pooled:
+                assert len(got) == min(M, len(rows[h])), f"{what} b={b} h={h}: kept {len(got)}"
+        total = sum(len(r) for r in rows)
+        n_keep = min(H * M, total)
+        if pooled:
+            assert sum(len(g) for g in gpu_keep[b]) == n_keep, f"{what} b={b}: pooled count"
+            pool_thr = np.sort(np.concatenate(rows))[total - n_keep] if 0 < n_keep < total else None
+        for h in range(H):
+            sym = np.setxor1d(ref[h], np.asarray(gpu_keep[b][h]))
+            if sym.size == 0:
+                continue
+            if pooled:
+                assert pool_thr is not None, f"{what} b={b} h={h}: everything fits, yet the sets differ"
+                thr = pool_thr
+            else:
+                thr = np.sort(rows[h])[len(rows[h]) - min(M, len(rows[h]))]
+            off = np.abs(rows[h][sym] - thr)
+            band = rtol * abs(thr) + ATOL
+            assert (off <= band).all(), (
+                f"{what} b={b} h={h}: {sym.size} differing tokens, {(off > band).sum()} outside the band "
+                f"(thr {thr!r}, worst {off.max()!r})")
+            differ += sym.size
+    return differ
