@@ -167,6 +167,25 @@ def main():
     torch.cuda.synchronize()
     t_score_lse = sum(e[0].elapsed_time(e[1]) for e in ev2) / len(ev2) * 1e-3
 
+    # ---- the ragged entry point on the same inputs (every head holds N rows before the step):
+    # lengths and budgets are read from device memory; pooled = head-wise non-uniform retention
+    n_ctx = torch.full((nb, w.Hkv), w.N, dtype=torch.int32, device=dev)
+    budgets = torch.full((nb,), w.M, dtype=torch.int32, device=dev)
+    n_kept = torch.empty((nb, w.Hkv), dtype=torch.int32, device=dev)
+    t_ragged = {}
+    for tag, select in (("per_head", ep.SELECT_PER_HEAD), ("pooled", ep.SELECT_POOLED)):
+        wsr = ep.alloc_ragged_workspace(prm, select)
+        ev3 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.stage_reps)]
+        for rep in range(args.stage_reps + 1):
+            kp.copy_(kfresh), vp.copy_(vfresh)
+            e = ev3[rep - 1] if rep > 0 else [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            e[0].record()
+            ep.epicache_evict_step_ragged(prm, select, q0, kp, vp, n_ctx, budgets, n_kept, wsr)
+            e[1].record()
+        torch.cuda.synchronize()
+        t_ragged[tag] = sum(e[0].elapsed_time(e[1]) for e in ev3) / len(ev3) * 1e-3
+        del wsr
+
     nbh = nb * w.Hkv
     flops_score = 2.0 * w.R * w.N * w.d * nbh                      # one Q.K^T (algorithmic)
     bytes_topk = nbh * (4.0 * w.N + 4.0 * w.M)
@@ -181,6 +200,9 @@ def main():
         "topk": {"ms": t_topk * 1e3, "gbs": bytes_topk / t_topk / 1e9},
         "compact": {"ms": t_compact * 1e3, "gbs": bytes_compact / t_compact / 1e9,
                     "frac_hbm_peak": bytes_compact / t_compact / 1e9 / PEAK_HBM_GBS},
+        "evict_step_ragged": {"ms_per_head": t_ragged["per_head"] * 1e3, "ms_pooled": t_ragged["pooled"] * 1e3,
+                              "note": "epicache_evict_step_ragged on the same inputs, lengths and budgets read "
+                                      "from device memory; not part of the timed step"},
         "select_plus_compact": {"ms": (t_topk + t_compact) * 1e3,
                                 "gbs": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9,
                                 "frac_hbm_peak": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9 / PEAK_HBM_GBS},
