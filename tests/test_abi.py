@@ -101,6 +101,43 @@ def test_null_misaligned_and_small_workspace_are_rejected():
     assert lib.epicache_evict_step(ctypes.byref(prm), a, a, a, None, None, a, need, None) == ep.ERR_INVALID_ARG
 
 
+def test_ragged_calls_validate_on_the_host():
+    prm = _params()
+    lib = ep.load()
+    a, b = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
+    for select, cap in ((ep.SELECT_PER_HEAD, 512), (ep.SELECT_POOLED, 640)):   # min(M, N) and min(Hkv*M, N)
+        need, got_cap = ep.epicache_ragged_workspace_size(prm, select)
+        assert got_cap == cap and need % 256 == 0 and need > ep.epicache_workspace_size(prm) - 256
+    need, _ = ep.epicache_ragged_workspace_size(prm, ep.SELECT_POOLED)
+    sz, cap = ctypes.c_size_t(), ctypes.c_int32()
+    assert lib.epicache_ragged_workspace_size(ctypes.byref(prm), 2, ctypes.byref(sz), ctypes.byref(cap)) == \
+        ep.ERR_INVALID_ARG                                                      # unknown selection rule
+    assert lib.epicache_ragged_workspace_size(ctypes.byref(prm), 0, None, ctypes.byref(cap)) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, None, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, a, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_select_ragged(ctypes.byref(prm), 1, a, a, None, a, None, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_select_ragged(ctypes.byref(prm), 1, a, a, None, a, a, a, need - 1, None) == \
+        ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_select_ragged(ctypes.byref(prm), 5, a, a, None, a, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_compact_ragged(ctypes.byref(prm), 0, a, a, a, a, None, 0, None) == ep.ERR_INVALID_ARG  # K is V
+    assert lib.epicache_compact_ragged(ctypes.byref(prm), 0, a, None, a, b, None, 0, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, None, None, None, a, need,
+                                          None) == ep.ERR_INVALID_ARG          # n_kept is required
+    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, a, None, None, a, need - 1,
+                                          None) == ep.ERR_WORKSPACE_TOO_SMALL
+    bad = _params(budget=0)
+    assert lib.epicache_evict_step_ragged(ctypes.byref(bad), 1, a, a, b, a, None, a, None, None, a, need,
+                                          None) == ep.ERR_INVALID_ARG
+    # pooled selection keeps its per-head counters on chip: at most 1024 KV heads
+    q = torch.empty(1, 2048, 1, 8, dtype=torch.float32)
+    k = torch.empty(1, 2048, 16, 8, dtype=torch.float32)
+    wide = ep.make_params(q, k, n_cached=0, n_block=16, budget=4)
+    assert ep.epicache_ragged_workspace_size(wide, ep.SELECT_PER_HEAD)[1] == 4
+    with pytest.raises(ep.EpicacheError) as ei:
+        ep.epicache_ragged_workspace_size(wide, ep.SELECT_POOLED)
+    assert ei.value.status == ep.ERR_UNSUPPORTED
+
+
 def test_binding_raises_with_status():
     with pytest.raises(ep.EpicacheError) as ei:
         ep.epicache_workspace_size(_params(budget=-3))

@@ -264,6 +264,38 @@ def test_evict_step_ragged_bf16_layer(select, pooled):
     say(f"  tokens differing inside the band: {differ}; kept per head of item 0: {n_kept[0].tolist()}")
 
 
+def test_layers_with_eq6_budgets_fold_into_one_launch():
+    """Sec. 3.2: layers whose budgets M_l come from Eq. 6 hold M_l + B rows before the step; folded into the
+    batch axis they are one ragged launch, checked against the uniform oracle step of each layer."""
+    w = wl("llama31_8b", E=2, Hq=8, Hkv=2, p=32, M=384, B=256, L=3)
+    m_l = ep.epicache_layer_budgets([0.12, 0.31, 0.05], 2.0, w.M)
+    assert sum(m_l) == w.L * w.M and len(set(m_l)) == 3
+    n_max, m_max = max(m_l) + w.B, max(m_l)
+    say(f"folded layers, budgets {m_l}")
+    qs, ks, vs, n_ctx, budgets = [], [], [], [], []
+    for l in range(w.L):
+        q, k, v = synth.make_layer(w, layer=l, n_ctx=m_l[l] + w.B, capacity=n_max)
+        qs.append(q), ks.append(k), vs.append(v)
+        n_ctx += [[m_l[l] + w.B] * w.Hkv] * w.E
+        budgets += [m_l[l]] * w.E
+    q, k, v = torch.cat(qs), torch.cat(ks), torch.cat(vs)
+    scores, keep, n_kept, kd, vd = run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, ep.SELECT_PER_HEAD,
+                                                   orc.REDUCE_SUM)
+    for l in range(w.L):
+        sl = slice(l * w.E, (l + 1) * w.E)
+        N, M = m_l[l] + w.B, m_l[l]
+        o_scores, o_keep, o_k, o_v = orc.evict_step(*pu.oracle_inputs(qs[l], ks[l]), None, N, M, orc.REDUCE_SUM,
+                                                    k_bits=synth.raw_bits_numpy(ks[l]),
+                                                    v_bits=synth.raw_bits_numpy(vs[l]))
+        assert (n_kept[sl] == M).all()
+        pu.assert_scores_close(scores[sl, :, :N], o_scores, pu.RTOL_BF16, f"layer {l}")
+        pu.assert_keep_matches(keep[sl, :, :M], o_scores, M, pu.RTOL_BF16, f"layer {l}")
+        same = (keep[sl, :, :M] == o_keep).all(axis=2)
+        assert same.any()
+        np.testing.assert_array_equal(synth.raw_bits_numpy(kd[sl])[:, :, :M][same], o_k[same])
+        np.testing.assert_array_equal(synth.raw_bits_numpy(vd[sl])[:, :, :M][same], o_v[same])
+
+
 def test_pooled_sweep_feeds_its_own_counts_forward():
     """Head-wise non-uniform retention over a block sweep: the per-head counts one step leaves on the
     device are the next step's cached lengths (no host round trip inside the library); the layer as a
