@@ -305,3 +305,52 @@ def evict_step_ragged(q, k, v, n_ctx, budgets, pooled: bool, reduce: int = REDUC
     kk = [[ks[b, h][idx] for h, idx in enumerate(per_head)] for b, per_head in enumerate(keep)]
     vv = [[vs[b, h][idx] for h, idx in enumerate(per_head)] for b, per_head in enumerate(keep)]
     return rows, keep, kk, vv
+
+
+# ---------------------------------------------------------------------------------------------
+# The patch's own keys in the denominator.  In a forward pass of the model the patch token
+# x_{n+1+t} attends causally to the n context tokens and to the patch tokens up to itself, so the
+# attention weight of Eq. 1 is normalised over n + t + 1 keys.  (Sec. 2.3 only says that the patch
+# queries attend back to the context; score() above takes that literally and normalises over the
+# context alone.)  The patch is appended after the context (Sec. 2.3): its keys sit in rows
+# [n_ctx, n_ctx + p) of k[b, h], and they are never scored or kept themselves.
+# ---------------------------------------------------------------------------------------------
+
+def attention_weights_causal_patch(q_rows, k_ctx, k_patch, scale: float, p: int) -> np.ndarray:
+    """Weights on the N context keys for the R = G*p query rows (row r = g*p + t is patch token t).
+
+    Row r's softmax runs over the N context keys and the patch keys 0..t.  Returns [R, N].
+    """
+    R, N = q_rows.shape[0], k_ctx.shape[0]
+    out = np.empty((R, N), dtype=np.float64)
+    for r in range(R):
+        t = r % p
+        keys = np.concatenate([k_ctx, k_patch[:t + 1]])
+        z = scale * (keys @ q_rows[r])
+        z = z - z.max()
+        e = np.exp(z)
+        out[r] = e[:N] / e.sum()
+    return out
+
+
+def score_causal_patch(q, k, n_ctx: int, reduce: int = REDUCE_MAX, scale: float | None = None) -> np.ndarray:
+    """Eq. 1 with the patch's own causal keys in every softmax denominator.
+
+    q [nb, Hq, p, d]; k [nb, Hkv, C >= n_ctx + p, d] with the patch keys in rows n_ctx .. n_ctx+p-1.
+    Returns float64 [nb, Hkv, n_ctx].
+    """
+    nb, Hq, p, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    assert k.shape[2] >= n_ctx + p
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((nb, Hkv, n_ctx), dtype=np.float64)
+    for b in range(nb):
+        for h in range(Hkv):
+            rows = np.asarray(q[b, h * G:(h + 1) * G], dtype=np.float64).reshape(G * p, d)
+            ctx = np.asarray(k[b, h, :n_ctx], dtype=np.float64)
+            patch = np.asarray(k[b, h, n_ctx:n_ctx + p], dtype=np.float64)
+            attn = attention_weights_causal_patch(rows, ctx, patch, scale, p)
+            out[b, h] = attn.max(axis=0) if reduce == REDUCE_MAX else attn.sum(axis=0)
+    return out
