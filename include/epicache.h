@@ -74,6 +74,11 @@ typedef struct epicache_params {
   int32_t dtype;          /* epicache_dtype of Q, K, V                                        */
   int32_t reduce;         /* epicache_reduce over the G*p rows that vote for one KV head      */
   float softmax_scale;    /* logit scale; 0 selects 1/sqrt(head_dim)                          */
+  int32_t causal_patch;   /* 0: softmax over the N context keys only.  1: rows [N, N+patch_len) of */
+                          /* K[b,h] hold the patch's own keys and patch token t also attends to    */
+                          /* patch keys 0..t, as in the model's forward pass (Sec. 2.3); only the  */
+                          /* N context rows are scored.  Capacity must then cover N + patch_len.   */
+  int32_t reserved;       /* must be 0                                                        */
   int64_t q_stride_b, q_stride_h, q_stride_t;    /* Q strides: batch, head, token             */
   int64_t kv_stride_b, kv_stride_h, kv_stride_t; /* K/V strides; capacity = rows per head     */
 } epicache_params;
@@ -97,7 +102,8 @@ EPICACHE_API int epicache_score(const epicache_params* params, const void* q, co
  * keys that query attended to, as a fused attention kernel returns it for the patched prompt's
  * forward pass.  If that sum runs over more keys than the N context rows (the patch's own causal
  * keys), the scores are the attention weights under that larger denominator.  Needs the same
- * workspace as epicache_score. */
+ * workspace as epicache_score.  causal_patch must be 0: the supplied normaliser already fixes the
+ * denominator. */
 EPICACHE_API int epicache_score_lse(const epicache_params* params, const void* q, const void* k,
                    const float* row_lse, float* scores, void* workspace, size_t workspace_bytes,
                    void* hip_stream);
@@ -146,6 +152,7 @@ EPICACHE_API int epicache_evict_step_lse(const epicache_params* params, const vo
  * the strides of `scores`, the launch grids and the capacity check) and params->budget bounds
  * every per-item budget.
  *   n_ctx   [n_batch, n_kv_heads] int32: context rows of (b, h); values are clamped to 0..N_max
+ *           (with causal_patch the patch keys of (b, h) follow its own context: rows n_ctx .. n_ctx+p-1)
  *   budgets [n_batch] int32: M_b, clamped to 1..params->budget; NULL = params->budget everywhere
  *   scores  [n_batch, n_kv_heads, N_max] float32: entries at or beyond n_ctx[b,h] are not written
  *   keep    [n_batch, n_kv_heads, keep_capacity] int32: the first n_kept[b,h] entries are valid

@@ -45,6 +45,8 @@ class Params(ctypes.Structure):
         ("dtype", ctypes.c_int32),
         ("reduce", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
+        ("causal_patch", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("q_stride_b", ctypes.c_int64),
         ("q_stride_h", ctypes.c_int64),
         ("q_stride_t", ctypes.c_int64),
@@ -113,13 +115,13 @@ def version() -> str:
 
 
 def make_params(q: torch.Tensor, k: torch.Tensor, n_cached: int, n_block: int, budget: int,
-                reduce: int = REDUCE_MAX, softmax_scale: float = 0.0) -> Params:
+                reduce: int = REDUCE_MAX, softmax_scale: float = 0.0, causal_patch: int = 0) -> Params:
     """Fill epicache_params from Q [nb,Hq,p,d] and K [nb,Hkv,C,d] (shapes and strides only)."""
     nb, Hq, p, d = q.shape
     assert q.dtype == k.dtype and q.stride(3) == 1 and k.stride(3) == 1
     dtype = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}[q.dtype]
     return Params(ctypes.sizeof(Params), nb, Hq, k.shape[1], d, n_cached, n_block, budget, p, dtype,
-                  reduce, softmax_scale, q.stride(0), q.stride(1), q.stride(2),
+                  reduce, softmax_scale, causal_patch, 0, q.stride(0), q.stride(1), q.stride(2),
                   k.stride(0), k.stride(1), k.stride(2))
 
 

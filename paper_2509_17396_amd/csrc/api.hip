@@ -43,8 +43,10 @@ int make_plan(const epicache_params* prm, Plan* out) {
   if (prm->reduce != EPICACHE_REDUCE_MAX && prm->reduce != EPICACHE_REDUCE_SUM)
     return EPICACHE_ERR_INVALID_ARG;
   if (!(prm->softmax_scale >= 0.0f) || isinf(prm->softmax_scale)) return EPICACHE_ERR_INVALID_ARG;
+  if ((prm->causal_patch != 0 && prm->causal_patch != 1) || prm->reserved != 0) return EPICACHE_ERR_INVALID_ARG;
   const int64_t N64 = (int64_t)prm->n_cached + prm->n_block;
   if (N64 < 1) return EPICACHE_ERR_INVALID_ARG;
+  const int64_t rows64 = N64 + (prm->causal_patch ? prm->patch_len : 0);  // K rows a head must hold
 
   Plan pl;
   memset(&pl, 0, sizeof(pl));
@@ -57,6 +59,7 @@ int make_plan(const epicache_params* prm, Plan* out) {
   pl.M = prm->budget;
   pl.dtype = prm->dtype;
   pl.reduce = prm->reduce;
+  pl.causal_patch = prm->causal_patch;
   pl.elem = prm->dtype == EPICACHE_DTYPE_F32 ? 4 : 2;
   pl.qsb = prm->q_stride_b, pl.qsh = prm->q_stride_h, pl.qst = prm->q_stride_t;
   pl.ksb = prm->kv_stride_b, pl.ksh = prm->kv_stride_h, pl.kst = prm->kv_stride_t;
@@ -68,9 +71,9 @@ int make_plan(const epicache_params* prm, Plan* out) {
   if (pl.qst < pl.d || pl.kst < pl.d) return EPICACHE_ERR_INVALID_ARG;
   if (pl.qst > (1 << 20) || pl.kst > (1 << 20)) return EPICACHE_ERR_UNSUPPORTED;  // 32-bit row offsets in the kernels
   if (pl.qsh < pl.qst * (int64_t)(pl.p - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
-  if (pl.ksh < pl.kst * (N64 - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.ksh < pl.kst * (rows64 - 1) + pl.d) return EPICACHE_ERR_INVALID_ARG;
   if (pl.nb > 1 && (pl.qsb < pl.qsh * (int64_t)(pl.Hq - 1) + pl.qst * (int64_t)(pl.p - 1) + pl.d ||
-                    pl.ksb < pl.ksh * (int64_t)(pl.Hkv - 1) + pl.kst * (N64 - 1) + pl.d))
+                    pl.ksb < pl.ksh * (int64_t)(pl.Hkv - 1) + pl.kst * (rows64 - 1) + pl.d))
     return EPICACHE_ERR_INVALID_ARG;
 
   // supported envelope
@@ -191,6 +194,7 @@ int epicache_score_lse(const epicache_params* params, const void* q, const void*
   int st = make_plan(params, &pl);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !row_lse || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (pl.causal_patch) return EPICACHE_ERR_INVALID_ARG;  // the supplied normaliser already fixes the denominator
   if (misaligned(q) || misaligned(k) || misaligned(row_lse) || misaligned(scores) || misaligned(workspace))
     return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
@@ -237,6 +241,7 @@ static int evict_step_impl(const epicache_params* params, const void* q, void* k
   int st = make_plan(params, &pl);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !v || !workspace || (with_lse && !row_lse)) return EPICACHE_ERR_INVALID_ARG;
+  if (with_lse && pl.causal_patch) return EPICACHE_ERR_INVALID_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) ||
       misaligned(scores_opt) || misaligned(keep_idx_opt) || misaligned(row_lse))
     return EPICACHE_ERR_INVALID_ARG;

@@ -19,6 +19,7 @@ struct Plan {
   int M;        // budget
   int n_keep;   // min(M, N)
   int dtype, reduce;
+  int causal_patch;  // the p rows after a head's context are the patch's keys, seen causally by the queries
   int elem;     // bytes per element of Q/K/V
   float c2;     // softmax scale * log2(e): logits are handled in base 2
   int64_t qsb, qsh, qst, ksb, ksh, kst;  // strides in elements

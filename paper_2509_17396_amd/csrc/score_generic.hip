@@ -44,6 +44,19 @@ __global__ __launch_bounds__(256) void score_generic_stats(const T* __restrict__
     D = D * exp2f(m - mn) + exp2f(z - mn);  // first term: exp2(-inf) * 0 = 0
     m = mn;
   }
+  if (pl.causal_patch && N > 0) {
+    // the patch's own keys follow the context; token t = r % p sees patch keys 0..t
+    const int t = r % pl.p;
+    for (int j = lane; j <= t; j += 64) {
+      const T* krow = kbase + (int64_t)(N + j) * pl.kst;
+      float dot = 0.f;
+      for (int c = 0; c < pl.d; c++) dot = fmaf(qs[wave][c], to_f32(krow[c]), dot);
+      const float z = dot * pl.c2;
+      const float mn = fmaxf(m, z);
+      D = D * exp2f(m - mn) + exp2f(z - mn);
+      m = mn;
+    }
+  }
   for (int off = 32; off >= 1; off >>= 1) {
     const float mo = __shfl_xor(m, off), Do = __shfl_xor(D, off);
     const float mn = fmaxf(m, mo);

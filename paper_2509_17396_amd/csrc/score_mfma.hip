@@ -391,6 +391,36 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
     }
   }
 
+  if (pl.causal_patch && split == 0) {
+    // the patch's own keys follow the context rows; the query of patch token t = r % p sees patch
+    // keys 0..t (Sec. 2.3: the patch is appended after the block and attends causally)
+    const int ptiles = (pl.p + kKeyTile - 1) / kKeyTile;
+    for (int pt = 0; pt < ptiles; pt++) {
+      const int nrows = min(kKeyTile, pl.p - pt * kKeyTile);
+      const unsigned char* tile = kbase + (size_t)(N + pt * kKeyTile) * kstride;
+      __syncthreads();  // every wave is done reading the buffer this tile lands in
+      ST::run_rows(lds0, wave, lane, [=](int row) { return tile + (size_t)min(row, nrows - 1) * kstride; });
+      wait_vmem();
+      __syncthreads();
+      if (active) {
+        for (int ks = 0; ks < 2; ks++) {
+          bf16x8 kf[KS];
+          read_frags<HD>(kf, lds, ks, l32, hi);
+#pragma unroll
+          for (int s = 0; s < NQ; s++) {
+            const int t_row = (row0 + s * 32 + l32) % pl.p;
+            f32x16 acc;
+            mfma_chain<KS>(acc, kf, qf[s]);
+#pragma unroll
+            for (int v = 0; v < 16; v++)
+              if (pt * kKeyTile + ks * 32 + (v >> 2) * 8 + hi * 4 + (v & 3) > t_row) acc[v] = kMasked;
+            stats_fold(acc, st[s], c2);
+          }
+        }
+      }
+    }
+  }
+
   if (!active) return;
 #pragma unroll
   for (int s = 0; s < NQ; s++) {

@@ -33,8 +33,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_params_struct_matches_header_layout():
-    assert ctypes.sizeof(ep.Params) == 4 * 12 + 8 * 6
-    assert ep.Params.q_stride_b.offset == 48
+    assert ctypes.sizeof(ep.Params) == 4 * 14 + 8 * 6
+    assert ep.Params.q_stride_b.offset == 56
 
 
 def test_status_strings():
@@ -58,6 +58,9 @@ def test_workspace_size_is_host_only_and_monotone():
     ("reduce", 2, ep.ERR_INVALID_ARG),
     ("softmax_scale", -1.0, ep.ERR_INVALID_ARG),
     ("softmax_scale", float("nan"), ep.ERR_INVALID_ARG),
+    ("causal_patch", 2, ep.ERR_INVALID_ARG),
+    ("causal_patch", 1, ep.ERR_INVALID_ARG),      # capacity 640 = N: no room for the 16 patch keys
+    ("reserved", 1, ep.ERR_INVALID_ARG),
     ("n_block", -600, ep.ERR_INVALID_ARG),
     ("kv_stride_t", 64, ep.ERR_INVALID_ARG),     # rows would overlap
     ("kv_stride_t", 132, ep.ERR_INVALID_ARG),    # not a multiple of 8

@@ -26,9 +26,9 @@ def wl(name, **kw):
     return synth.WORKLOADS[name].scaled(**kw)
 
 
-def gpu_score(q, k, N, M, reduce, scale=0.0):
+def gpu_score(q, k, N, M, reduce, scale=0.0, causal_patch=0):
     prm = ep.make_params(q, k, n_cached=min(M, N), n_block=N - min(M, N), budget=M, reduce=reduce,
-                         softmax_scale=scale)
+                         softmax_scale=scale, causal_patch=causal_patch)
     ws = ep.alloc_workspace(prm)
     scores = torch.full((q.shape[0], k.shape[1], N), float("nan"), dtype=torch.float32, device=DEV)
     ep.epicache_score(prm, q, k, scores, ws)
@@ -78,6 +78,58 @@ def test_score_matches_oracle(case, reduce):
     want = orc.score(qq, kk, N, reduce)
     worst = pu.assert_scores_close(got, want, pu.rtol_for(q.dtype), name)
     say(f"  max rel err {worst:.3e}")
+
+
+CAUSAL_CASES = [
+    # name, base workload, overrides, number of context rows (the p patch keys follow them)
+    ("fp32_generic", "tiny", dict(E=2, Hq=6, Hkv=2, p=5, d=40), 203),
+    ("fp32_generic_long_patch", "tiny", dict(E=1, Hq=2, Hkv=1, p=150, d=16), 70),
+    ("bf16_stream_R192_p64", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=64), 640),
+    ("bf16_stream_p37_ragged_keys", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=37), 1000),
+    ("bf16_stream_several_splits", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=32), 3000),
+    ("bf16_keys_stationary_p100_two_patch_tiles", "llama31_8b", dict(E=1, Hq=8, Hkv=2, p=100), 777),
+    ("bf16_d64_p48", "llama32_3b", dict(E=2, Hq=4, Hkv=2, p=48, d=64), 333),
+    ("bf16_one_context_key", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=16), 1),
+]
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+@pytest.mark.parametrize("case", CAUSAL_CASES, ids=[c[0] for c in CAUSAL_CASES])
+def test_score_with_causal_patch_keys_matches_oracle(case, reduce):
+    """causal_patch = 1: the patch's own keys (rows N .. N+p-1) join every softmax denominator causally."""
+    name, base, over, N = case
+    w = wl(base, **over)
+    say(f"score causal_patch {name} reduce={reduce}")
+    q, k, _ = synth.make_layer(w, layer=0, n_ctx=N + w.p)
+    got = gpu_score(q.to(DEV), k.to(DEV), N, w.M, reduce, causal_patch=1)
+    qq, kk = pu.oracle_inputs(q, k)
+    want = orc.score_causal_patch(qq, kk, N, reduce)
+    worst = pu.assert_scores_close(got, want, pu.rtol_for(q.dtype), name)
+    plain = orc.score(qq, kk, N, reduce)
+    assert (want <= plain).all() and (want < plain * (1 - 1e-3)).any()   # the flag really matters here
+    say(f"  max rel err {worst:.3e}")
+
+
+def test_evict_step_with_causal_patch_keys():
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=64, M=384, B=256)
+    N = w.M + w.B
+    say("evict_step causal_patch")
+    q, k, v = synth.make_layer(w, layer=3, n_ctx=N + w.p)
+    qd, kd, vd = q.to(DEV), k.to(DEV).clone(), v.to(DEV).clone()
+    prm = ep.make_params(qd, kd, n_cached=w.M, n_block=w.B, budget=w.M, reduce=orc.REDUCE_MAX, causal_patch=1)
+    ws = ep.alloc_workspace(prm)
+    keep = torch.full((w.E, w.Hkv, w.M), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step(prm, qd, kd, vd, ws, None, keep)
+    torch.cuda.synchronize()
+    keep = keep.cpu().numpy()
+    o_scores = orc.score_causal_patch(*pu.oracle_inputs(q, k), N, orc.REDUCE_MAX)
+    differ = pu.assert_keep_matches(keep, o_scores, w.M, pu.RTOL_BF16, "causal")
+    kb = synth.raw_bits_numpy(k)
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd.cpu())[:, :, :w.M], orc.compact(kb, keep))
+    # the selection differs from the one under the context-only denominator: the flag reached the step
+    plain_keep = orc.topk(orc.score(*pu.oracle_inputs(q, k), N, orc.REDUCE_MAX).astype(np.float32), w.M)
+    assert (plain_keep != keep).any()
+    say(f"  tokens differing inside the band: {differ}")
 
 
 def test_score_explicit_scale_and_strided_views():

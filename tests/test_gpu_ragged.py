@@ -79,6 +79,30 @@ def test_score_ragged_matches_oracle(case, reduce):
     say(f"  max rel err {worst:.3e}")
 
 
+def test_score_ragged_with_causal_patch_keys():
+    """Every head's patch keys follow its own context rows (rows n_ctx .. n_ctx+p-1)."""
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=40)
+    n_max = 700
+    say("score_ragged causal_patch")
+    q, k, _ = synth.make_layer(w, layer=1, n_ctx=n_max + w.p)
+    n_ctx = lengths(12, w.E, w.Hkv, n_max, (n_max, 1, 64))
+    qd, kd = q.to(DEV), k.to(DEV)
+    prm = ep.make_params(qd, kd, n_cached=0, n_block=n_max, budget=7, reduce=orc.REDUCE_SUM, causal_patch=1)
+    ws = ep.alloc_workspace(prm)
+    scores = torch.full((w.E, w.Hkv, n_max), -7.0, dtype=torch.float32, device=DEV)
+    ep.epicache_score_ragged(prm, qd, kd, i32(n_ctx), scores, ws)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy()
+    qq, kk = pu.oracle_inputs(q, k)
+    for b in range(w.E):
+        for h in range(w.Hkv):
+            n = n_ctx[b, h]
+            G = w.Hq // w.Hkv
+            want = orc.score_causal_patch(qq[b:b + 1, h * G:(h + 1) * G], kk[b:b + 1, h:h + 1], n, orc.REDUCE_SUM)[0, 0]
+            pu.assert_scores_close(got[b, h, :n], want, pu.RTOL_BF16, f"b={b} h={h} n={n}")
+            assert (got[b, h, n:] == -7.0).all()
+
+
 # ------------------------------------------------------------------- select
 
 def gpu_select(scores_np, n_ctx, budgets, m_max, select):
