@@ -354,3 +354,31 @@ def score_causal_patch(q, k, n_ctx: int, reduce: int = REDUCE_MAX, scale: float 
             attn = attention_weights_causal_patch(rows, ctx, patch, scale, p)
             out[b, h] = attn.max(axis=0) if reduce == REDUCE_MAX else attn.sum(axis=0)
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# KeyDiff scoring (App. A.2, "KeyDiff"): an attention-free baseline that runs on the same
+# select / compact back end.  Per KV head the anchor is the average of the key states of all
+# context tokens; a token's score is minus the cosine similarity between its key and the anchor,
+# so keys that point away from the bulk are kept.
+# Reading where the text is silent: a zero key or a zero anchor has cosine 0.
+# ---------------------------------------------------------------------------------------------
+
+def score_keydiff(k, n_ctx) -> np.ndarray:
+    """k [nb, Hkv, C, d]; n_ctx an int or per-(b, h) lengths.  Returns float64 [nb, Hkv, max n_ctx];
+    entries at or beyond a head's own length are NaN."""
+    nb, Hkv = k.shape[:2]
+    lens = np.broadcast_to(np.asarray(n_ctx), (nb, Hkv))
+    out = np.full((nb, Hkv, int(lens.max())), np.nan, dtype=np.float64)
+    for b in range(nb):
+        for h in range(Hkv):
+            n = int(lens[b, h])
+            if n == 0:
+                continue
+            keys = np.asarray(k[b, h, :n], dtype=np.float64)
+            anchor = keys.sum(axis=0) / n
+            dots = keys @ anchor
+            norms = np.sqrt((keys * keys).sum(axis=1)) * math.sqrt(float(anchor @ anchor))
+            cos = np.divide(dots, norms, out=np.zeros(n), where=norms > 0)
+            out[b, h, :n] = -cos
+    return out
