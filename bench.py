@@ -186,6 +186,16 @@ def main():
         t_ragged[tag] = sum(e[0].elapsed_time(e[1]) for e in ev3) / len(ev3) * 1e-3
         del wsr
 
+    # ---- the attention-free KeyDiff scorer on the same K (second workload of the same back end)
+    ev4 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.stage_reps)]
+    for rep in range(args.stage_reps + 1):
+        e = ev4[rep - 1] if rep > 0 else [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        ep.epicache_score_keydiff(prm, kfresh, scores, ws)
+        e[1].record()
+    torch.cuda.synchronize()
+    t_keydiff = sum(e[0].elapsed_time(e[1]) for e in ev4) / len(ev4) * 1e-3
+
     nbh = nb * w.Hkv
     flops_score = 2.0 * w.R * w.N * w.d * nbh                      # one Q.K^T (algorithmic)
     bytes_topk = nbh * (4.0 * w.N + 4.0 * w.M)
@@ -203,6 +213,10 @@ def main():
         "evict_step_ragged": {"ms_per_head": t_ragged["per_head"] * 1e3, "ms_pooled": t_ragged["pooled"] * 1e3,
                               "note": "epicache_evict_step_ragged on the same inputs, lengths and budgets read "
                                       "from device memory; not part of the timed step"},
+        "score_keydiff": {"ms": t_keydiff * 1e3, "gbs": (nbh * w.N * (w.d * 2.0 + 4.0)) / t_keydiff / 1e9,
+                          "frac_hbm_peak": (nbh * w.N * (w.d * 2.0 + 4.0)) / t_keydiff / 1e9 / PEAK_HBM_GBS,
+                          "note": "epicache_score_keydiff: K read once + scores written as algorithmic bytes "
+                                  "(the kernels read K twice); not part of the timed step"},
         "select_plus_compact": {"ms": (t_topk + t_compact) * 1e3,
                                 "gbs": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9,
                                 "frac_hbm_peak": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9 / PEAK_HBM_GBS},

@@ -197,6 +197,17 @@ EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32
                                             int32_t* n_kept, float* scores_opt, int32_t* keep_idx_opt,
                                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* App. A.2 ("KeyDiff"): the attention-free baseline scorer, for the same epicache_topk /
+ * epicache_compact (or *_ragged) back end.  Per (b, h): anchor = mean of the key states of the
+ * context rows; scores[b,h,i] = -cos(K[b,h,i,:], anchor), so the keys that point away from the bulk
+ * score highest.  A zero key or a zero anchor gives 0.  Sums and products in fp32.
+ * n_ctx_opt: NULL, or per-(b,h) lengths [n_batch, n_kv_heads] as in the ragged calls (then
+ * n_cached + n_block is their upper bound and the pitch of a score row).  The query fields of
+ * params are not used but must still be valid (for instance n_q_heads = n_kv_heads, patch_len = 1). */
+EPICACHE_API int epicache_score_keydiff(const epicache_params* params, const void* k, const int32_t* n_ctx_opt,
+                                        float* scores, void* workspace, size_t workspace_bytes,
+                                        void* hip_stream);
+
 /* Sec. 3.2, Eq. 6 / Alg. 1 phase A2: split the global budget n_layers * budget over the layers in
  * proportion to sensitivity[l]^alpha (sensitivity[l] = 1 - sigma_l >= 0, alpha >= 0 the sharpness).
  * The paper's allocation is real-valued; here it is rounded by largest remainder (ties to the lower

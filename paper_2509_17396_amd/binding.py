@@ -25,7 +25,7 @@ ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
-    "epicache_evict_step_ragged", "epicache_status_string", "epicache_version",
+    "epicache_evict_step_ragged", "epicache_score_keydiff", "epicache_status_string", "epicache_version",
 )
 _INT_RETURNING = ENTRY_POINTS[:-2]
 
@@ -96,6 +96,7 @@ def load() -> ctypes.CDLL:
     lib.epicache_select_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_score_keydiff.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     for name in _INT_RETURNING:
         getattr(lib, name).restype = i32
     lib.epicache_status_string.argtypes = [i32]
@@ -221,6 +222,11 @@ def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budg
                                              _ptr(n_ctx), _ptr(budgets), _ptr(n_kept), _ptr(scores),
                                              _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step_ragged")
+
+
+def epicache_score_keydiff(params: Params, k, scores, workspace, n_ctx=None) -> None:
+    _check(load().epicache_score_keydiff(ctypes.byref(params), _ptr(k), _ptr(n_ctx), _ptr(scores),
+                                         _ptr(workspace), workspace.numel(), _stream()), "epicache_score_keydiff")
 
 
 def epicache_layer_budgets(sensitivity, alpha: float, budget: int):

@@ -121,6 +121,8 @@ int make_plan(const epicache_params* prm, Plan* out) {
   pl.off_keep = off;
   off += align256((size_t)nbh * pl.n_keep * sizeof(int32_t));
   pl.ws_total = off;
+  const size_t keydiff = align256(keydiff_workspace_bytes(pl));
+  if (pl.ws_total < keydiff) pl.ws_total = keydiff;
   pl.keep_stride = pl.n_keep;
   *out = pl;
   return EPICACHE_OK;
@@ -145,7 +147,7 @@ static int make_ragged_plan(const epicache_params* prm, int32_t select, Plan* ou
   off += align256((size_t)nbh * pl.keep_stride * sizeof(int32_t));
   pl.off_select = off;
   off += align256(select_ragged_record_bytes(pl));
-  pl.ws_total = off;
+  if (pl.ws_total < off) pl.ws_total = off;
   *out = pl;
   return EPICACHE_OK;
 }
@@ -204,6 +206,20 @@ int epicache_score_lse(const epicache_params* params, const void* q, const void*
   if (launch_lse_to_stats(pl, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
   hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, true, stream)
                              : launch_score_generic(pl, q, k, scores, stats, true, stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_score_keydiff(const epicache_params* params, const void* k, const int32_t* n_ctx_opt,
+                           float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!k || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(k) || misaligned(n_ctx_opt) || misaligned(scores) || misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < keydiff_workspace_bytes(pl)) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  pl.n_ctx = n_ctx_opt;
+  hipError_t e = launch_score_keydiff(pl, k, scores, workspace, (hipStream_t)hip_stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 

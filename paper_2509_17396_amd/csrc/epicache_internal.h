@@ -63,6 +63,10 @@ hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);
 hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
                           hipStream_t stream);
 size_t select_ragged_record_bytes(const Plan& pl);
+// KeyDiff scoring: chunk sums of the keys live at the start of the workspace.
+size_t keydiff_workspace_bytes(const Plan& pl);
+hipError_t launch_score_keydiff(const Plan& pl, const void* k, float* scores, void* workspace,
+                                hipStream_t stream);
 // Ragged selection: per-(b, h) (select == per head) or per-b pooled thresholds, then the kept indices.
 hipError_t launch_select_ragged(const Plan& pl, int select, const float* scores, const int32_t* budgets,
                                 int32_t* keep, int32_t* n_kept, void* records, hipStream_t stream);
