@@ -382,3 +382,56 @@ def score_keydiff(k, n_ctx) -> np.ndarray:
             cos = np.divide(dots, norms, out=np.zeros(n), where=norms > 0)
             out[b, h, :n] = -cos
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Episode geometry on segment embeddings (Sec. 3.1): centroid and centroid-closest segment of
+# every cluster (Stage 1, Eq. 3) and query-to-episode matching (Stage 3a, with the Stage 3b rule
+# that a query too far from every centroid opens a new episode).  The embeddings and the cluster
+# assignment are inputs: the encoder and K-Means are outside this library.
+# Readings: ties go to the lower index; an empty cluster has a zero centroid and medoid -1; the
+# cosine with a zero vector is 0.
+# ---------------------------------------------------------------------------------------------
+
+def _cosine(u: np.ndarray, v: np.ndarray) -> float:
+    den = math.sqrt(float(u @ u)) * math.sqrt(float(v @ v))
+    return float(u @ v) / den if den > 0 else 0.0
+
+
+def episode_medoids(emb, assign, E: int):
+    """Eq. 3.  emb [K, D], assign [K] in 0..E-1.  Returns (centroids float64 [E, D], medoid int32 [E]):
+    centroid = mean of the member embeddings, medoid = member with the largest cosine to it."""
+    emb = np.asarray(emb, dtype=np.float64)
+    K, D = emb.shape
+    cent = np.zeros((E, D), dtype=np.float64)
+    med = np.full(E, -1, dtype=np.int32)
+    for e in range(E):
+        members = [k for k in range(K) if assign[k] == e]
+        if not members:
+            continue
+        cent[e] = emb[members].sum(axis=0) / len(members)
+        best = -np.inf
+        for k in members:                      # ascending k, strict improvement: ties keep the lower k
+            c = _cosine(emb[k], cent[e])
+            if c > best:
+                best, med[e] = c, k
+    return cent, med
+
+
+def match_queries(queries, centroids, tau: float = -np.inf):
+    """Stage 3a: e = argmax_e cos(q, c_e) (ties -> lower e); Stage 3b: -1 if that cosine is below tau.
+    Returns (episode int32 [nq], cosine float64 [nq])."""
+    queries = np.asarray(queries, dtype=np.float64)
+    centroids = np.asarray(centroids, dtype=np.float64)
+    nq = queries.shape[0]
+    ep = np.empty(nq, dtype=np.int32)
+    cs = np.empty(nq, dtype=np.float64)
+    for i in range(nq):
+        best, arg = -np.inf, -1
+        for e in range(centroids.shape[0]):
+            c = _cosine(queries[i], centroids[e])
+            if c > best:
+                best, arg = c, e
+        cs[i] = best
+        ep[i] = arg if best >= tau else -1
+    return ep, cs
