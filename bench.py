@@ -196,6 +196,26 @@ def main():
     torch.cuda.synchronize()
     t_keydiff = sum(e[0].elapsed_time(e[1]) for e in ev4) / len(ev4) * 1e-3
 
+    # ---- episode geometry (Sec. 3.1 Eq. 3 and Stage 3a) at the scale of one long conversation:
+    # 2048 segment embeddings of dimension 1024 in E clusters, 256 queries to match
+    gen = torch.Generator(device=dev).manual_seed(7)
+    emb = torch.randn(2048, 1024, device=dev, generator=gen)
+    assign = torch.randint(0, w.E, (2048,), device=dev, generator=gen, dtype=torch.int32)
+    cents = torch.empty(w.E, 1024, device=dev)
+    med = torch.empty(w.E, dtype=torch.int32, device=dev)
+    qs = torch.randn(256, 1024, device=dev, generator=gen)
+    matched = torch.empty(256, dtype=torch.int32, device=dev)
+    ev5 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.stage_reps)]
+    for rep in range(args.stage_reps + 1):
+        e = ev5[rep - 1] if rep > 0 else [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        ep.epicache_episode_medoids(emb, assign, w.E, cents, med)
+        e[1].record()
+        ep.epicache_match_queries(qs, cents, 0.0, matched)
+        e[2].record()
+    torch.cuda.synchronize()
+    t_medoids, t_match = (sum(e[i].elapsed_time(e[i + 1]) for e in ev5) / len(ev5) * 1e-3 for i in range(2))
+
     nbh = nb * w.Hkv
     flops_score = 2.0 * w.R * w.N * w.d * nbh                      # one Q.K^T (algorithmic)
     bytes_topk = nbh * (4.0 * w.N + 4.0 * w.M)
@@ -217,6 +237,9 @@ def main():
                           "frac_hbm_peak": (nbh * w.N * (w.d * 2.0 + 4.0)) / t_keydiff / 1e9 / PEAK_HBM_GBS,
                           "note": "epicache_score_keydiff: K read once + scores written as algorithmic bytes "
                                   "(the kernels read K twice); not part of the timed step"},
+        "episode_geometry": {"medoids_ms": t_medoids * 1e3, "match_ms": t_match * 1e3,
+                             "note": "2048 segments x 1024 dims in E clusters; 256 queries; latency-bound, "
+                                     "not part of the timed step"},
         "select_plus_compact": {"ms": (t_topk + t_compact) * 1e3,
                                 "gbs": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9,
                                 "frac_hbm_peak": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9 / PEAK_HBM_GBS},

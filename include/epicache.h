@@ -208,6 +208,25 @@ EPICACHE_API int epicache_score_keydiff(const epicache_params* params, const voi
                                         float* scores, void* workspace, size_t workspace_bytes,
                                         void* hip_stream);
 
+/* Sec. 3.1 Stage 1, Eq. 3: for every cluster e of segment embeddings, its centroid (mean of the member
+ * embeddings) and its centroid-closest member (largest cosine to the centroid; equal cosines: the
+ * lower segment index), the segment that serves as the episode's patched prompt.  The encoder and the
+ * clustering are the caller's: embeddings [n_segments, dim] fp32 and assignment [n_segments] int32 in
+ * 0..n_episodes-1 are inputs (values outside that range belong to no cluster).  Out: centroids_out
+ * [n_episodes, dim] fp32 and medoid_out [n_episodes] int32; an empty cluster gets a zero centroid and
+ * medoid -1.  All DEVICE pointers, dense.  dim <= 8192. */
+EPICACHE_API int epicache_episode_medoids(const float* embeddings, const int32_t* assignment,
+                                          int32_t n_segments, int32_t n_episodes, int32_t dim,
+                                          float* centroids_out, int32_t* medoid_out, void* hip_stream);
+
+/* Sec. 3.1 Stage 3a: episode_out[i] = argmax over e of cos(queries[i], centroids[e]) (equal cosines: the
+ * lower e); Stage 3b: -1 instead when that cosine is below tau (the query opens a new episode; pass
+ * -INFINITY to always match).  The cosine with a zero vector is 0.  cosine_out_opt, if not NULL,
+ * receives the best cosine.  queries [n_queries, dim], centroids [n_episodes, dim] fp32, dense, DEVICE. */
+EPICACHE_API int epicache_match_queries(const float* queries, const float* centroids, int32_t n_queries,
+                                        int32_t n_episodes, int32_t dim, float tau, int32_t* episode_out,
+                                        float* cosine_out_opt, void* hip_stream);
+
 /* Sec. 3.2, Eq. 6 / Alg. 1 phase A2: split the global budget n_layers * budget over the layers in
  * proportion to sensitivity[l]^alpha (sensitivity[l] = 1 - sigma_l >= 0, alpha >= 0 the sharpness).
  * The paper's allocation is real-valued; here it is rounded by largest remainder (ties to the lower

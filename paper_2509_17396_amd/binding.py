@@ -25,7 +25,8 @@ ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
-    "epicache_evict_step_ragged", "epicache_score_keydiff", "epicache_status_string", "epicache_version",
+    "epicache_evict_step_ragged", "epicache_score_keydiff",
+    "epicache_episode_medoids", "epicache_match_queries", "epicache_status_string", "epicache_version",
 )
 _INT_RETURNING = ENTRY_POINTS[:-2]
 
@@ -97,6 +98,8 @@ def load() -> ctypes.CDLL:
     lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_score_keydiff.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_episode_medoids.argtypes = [vp, vp, i32c, i32c, i32c, vp, vp, vp]
+    lib.epicache_match_queries.argtypes = [vp, vp, i32c, i32c, i32c, ctypes.c_float, vp, vp, vp]
     for name in _INT_RETURNING:
         getattr(lib, name).restype = i32
     lib.epicache_status_string.argtypes = [i32]
@@ -227,6 +230,20 @@ def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budg
 def epicache_score_keydiff(params: Params, k, scores, workspace, n_ctx=None) -> None:
     _check(load().epicache_score_keydiff(ctypes.byref(params), _ptr(k), _ptr(n_ctx), _ptr(scores),
                                          _ptr(workspace), workspace.numel(), _stream()), "epicache_score_keydiff")
+
+
+def epicache_episode_medoids(embeddings, assignment, n_episodes: int, centroids, medoid) -> None:
+    K, D = embeddings.shape
+    assert embeddings.dtype == torch.float32 and embeddings.is_contiguous() and assignment.dtype == torch.int32
+    _check(load().epicache_episode_medoids(_ptr(embeddings), _ptr(assignment), K, int(n_episodes), D,
+                                           _ptr(centroids), _ptr(medoid), _stream()), "epicache_episode_medoids")
+
+
+def epicache_match_queries(queries, centroids, tau: float, episode, cosine=None) -> None:
+    nq, D = queries.shape
+    assert queries.dtype == torch.float32 and queries.is_contiguous() and centroids.is_contiguous()
+    _check(load().epicache_match_queries(_ptr(queries), _ptr(centroids), nq, centroids.shape[0], D, float(tau),
+                                         _ptr(episode), _ptr(cosine), _stream()), "epicache_match_queries")
 
 
 def epicache_layer_budgets(sensitivity, alpha: float, budget: int):

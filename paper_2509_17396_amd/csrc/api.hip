@@ -394,6 +394,27 @@ int epicache_evict_step_ragged(const epicache_params* params, int32_t select, co
   return EPICACHE_OK;
 }
 
+int epicache_episode_medoids(const float* embeddings, const int32_t* assignment, int32_t n_segments,
+                             int32_t n_episodes, int32_t dim, float* centroids_out, int32_t* medoid_out,
+                             void* hip_stream) {
+  if (!embeddings || !assignment || !centroids_out || !medoid_out) return EPICACHE_ERR_INVALID_ARG;
+  if (n_segments < 1 || n_episodes < 1 || dim < 1) return EPICACHE_ERR_INVALID_ARG;
+  if (dim > 8192 || n_episodes > 65535) return EPICACHE_ERR_UNSUPPORTED;  // centroid in LDS, one workgroup each
+  hipError_t e = launch_episode_medoids(embeddings, assignment, n_segments, n_episodes, dim, centroids_out,
+                                        medoid_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_match_queries(const float* queries, const float* centroids, int32_t n_queries, int32_t n_episodes,
+                           int32_t dim, float tau, int32_t* episode_out, float* cosine_out_opt,
+                           void* hip_stream) {
+  if (!queries || !centroids || !episode_out) return EPICACHE_ERR_INVALID_ARG;
+  if (n_queries < 1 || n_episodes < 1 || dim < 1 || tau != tau) return EPICACHE_ERR_INVALID_ARG;
+  hipError_t e = launch_match_queries(queries, centroids, n_queries, n_episodes, dim, tau, episode_out,
+                                      cosine_out_opt, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
 int epicache_layer_budgets(const double* sensitivity, int32_t n_layers, double alpha, int32_t budget,
                            int32_t* budgets_out) {
   if (!sensitivity || !budgets_out || n_layers < 1 || budget < 1) return EPICACHE_ERR_INVALID_ARG;

@@ -71,4 +71,10 @@ hipError_t launch_score_keydiff(const Plan& pl, const void* k, float* scores, vo
 hipError_t launch_select_ragged(const Plan& pl, int select, const float* scores, const int32_t* budgets,
                                 int32_t* keep, int32_t* n_kept, void* records, hipStream_t stream);
 
+// Episode geometry on fp32 embeddings: cluster centroids + centroid-closest members, query matching.
+hipError_t launch_episode_medoids(const float* emb, const int32_t* assign, int K, int E, int D,
+                                  float* centroids, int32_t* medoid, hipStream_t stream);
+hipError_t launch_match_queries(const float* queries, const float* centroids, int nq, int E, int D, float tau,
+                                int32_t* episode, float* cosine_opt, hipStream_t stream);
+
 }  // namespace epicache

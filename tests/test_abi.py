@@ -141,6 +141,23 @@ def test_ragged_calls_validate_on_the_host():
     assert ei.value.status == ep.ERR_UNSUPPORTED
 
 
+def test_keydiff_and_episode_calls_validate_on_the_host():
+    prm = _params()
+    lib = ep.load()
+    a = ctypes.c_void_p(4096)
+    need = ep.epicache_workspace_size(prm)
+    assert lib.epicache_score_keydiff(ctypes.byref(prm), None, None, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score_keydiff(ctypes.byref(prm), a, None, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_score_keydiff(ctypes.byref(prm), a, ctypes.c_void_p(4100), a, a, need, None) == \
+        ep.ERR_INVALID_ARG
+    assert lib.epicache_episode_medoids(a, a, 10, 0, 8, a, a, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_episode_medoids(a, None, 10, 2, 8, a, a, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_episode_medoids(a, a, 10, 2, 10000, a, a, None) == ep.ERR_UNSUPPORTED
+    assert lib.epicache_match_queries(a, a, 0, 2, 8, 0.5, a, None, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_match_queries(a, a, 3, 2, 8, float("nan"), a, None, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_match_queries(a, a, 3, 2, 8, 0.5, None, None, None) == ep.ERR_INVALID_ARG
+
+
 def test_binding_raises_with_status():
     with pytest.raises(ep.EpicacheError) as ei:
         ep.epicache_workspace_size(_params(budget=-3))
