@@ -128,3 +128,60 @@ def test_config3_sweep_free_running_invariants():
         n_cached = n_keep
         assert n_cached == min(w.M, N)
     assert n_cached == w.M
+
+
+@pytest.mark.parametrize("select,pooled", [(ep.SELECT_PER_HEAD, False), (ep.SELECT_POOLED, True)],
+                         ids=["per_head", "pooled"])
+def test_config2_folded_ragged_step_as_benchmarked(select, pooled):
+    """The ragged entry point in the launch configuration bench.py times it in (28 layers x 4 episodes,
+    every head at N rows, budget M per item), plus a few shorter heads and smaller budgets mixed in.
+    Properties over the whole batch on the device; sampled batch items against the oracle."""
+    w = synth.WORKLOADS["llama32_3b"]
+    say(f"config 2 folded, ragged step, pooled={pooled}")
+    q, k0, v0 = synth.make_folded(w, range(w.L), device=DEV)
+    k, v = k0.clone(), v0.clone()
+    nb, H, N, M = w.L * w.E, w.Hkv, w.N, w.M
+    n_ctx = torch.full((nb, H), N, dtype=torch.int32, device=DEV)
+    budgets = torch.full((nb,), M, dtype=torch.int32, device=DEV)
+    n_ctx[3, 2], n_ctx[3, 5], n_ctx[40, 0], n_ctx[40, 7] = 1000, 0, 65, 4095
+    budgets[40], budgets[77] = 300, 1
+    prm = ep.make_params(q, k, n_cached=M, n_block=w.B, budget=M, reduce=orc.REDUCE_SUM)
+    _, cap = ep.epicache_ragged_workspace_size(prm, select)
+    ws = ep.alloc_ragged_workspace(prm, select)
+    scores = torch.full((nb, H, N), float("nan"), dtype=torch.float32, device=DEV)
+    keep = torch.full((nb, H, cap), -1, dtype=torch.int32, device=DEV)
+    n_kept = torch.full((nb, H), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step_ragged(prm, select, q, k, v, n_ctx, budgets, n_kept, ws, scores, keep)
+    torch.cuda.synchronize()
+    # counts, over the whole batch
+    want_total = torch.minimum(budgets.long() * H, n_ctx.long().sum(dim=1))
+    if pooled:
+        assert (n_kept.long().sum(dim=1) == want_total).all()
+    else:
+        assert (n_kept == torch.minimum(budgets[:, None].expand(-1, H), n_ctx)).all()
+    assert (n_kept >= 0).all() and (n_kept <= n_ctx).all() and n_kept.max() <= cap
+    # kept rows are valid, ascending, and the compaction is their bit-exact gather (device-side check)
+    pos = torch.arange(cap, device=DEV)[None, None, :]
+    valid = pos < n_kept[:, :, None]
+    assert ((keep >= 0) | ~valid).all() and ((keep < n_ctx[:, :, None]) | ~valid).all()
+    assert ((keep[:, :, 1:] > keep[:, :, :-1]) | ~valid[:, :, 1:]).all()
+    idx = keep.clamp(min=0).long().unsqueeze(-1).expand(-1, -1, -1, w.d)
+    rows = min(cap, N)
+    gk = torch.gather(k0, 2, idx[:, :, :rows]).view(torch.int16)
+    gv = torch.gather(v0, 2, idx[:, :, :rows]).view(torch.int16)
+    m = valid[:, :, :rows, None].expand(-1, -1, -1, w.d)
+    assert torch.equal(torch.where(m, gk, 0), torch.where(m, k[:, :, :rows].view(torch.int16), 0))
+    assert torch.equal(torch.where(m, gv, 0), torch.where(m, v[:, :, :rows].view(torch.int16), 0))
+    # sampled batch items against the oracle (all heads of the item: the pool spans them)
+    differ = 0
+    for b in (0, 3, 40, 77, nb - 1):
+        say(f"  oracle on item {b}")
+        lens = n_ctx[b].tolist()
+        rows_o = orc.score_ragged(synth.to_f64_numpy(q[b:b + 1]), synth.to_f64_numpy(k0[b:b + 1]), [lens],
+                                  orc.REDUCE_SUM)
+        for h in range(H):
+            if lens[h]:
+                pu.assert_scores_close(scores[b, h, :lens[h]].cpu().numpy(), rows_o[0][h], pu.RTOL_BF16, f"b={b} h={h}")
+        got = [[keep[b, h, :int(n_kept[b, h])].cpu().numpy() for h in range(H)]]
+        differ += pu.assert_ragged_keep_matches(got, rows_o, [int(budgets[b])], pooled, pu.RTOL_BF16, f"item {b}")
+    say(f"  kept-set differences inside the band: {differ}; rows per head of item 0: {n_kept[0].tolist()}")
