@@ -171,10 +171,11 @@ EPICACHE_API int epicache_ragged_workspace_size(const epicache_params* params, i
                                                 size_t* bytes_out, int32_t* keep_capacity_out);
 
 /* Eq. 1 as epicache_score, over the first n_ctx[b,h] rows of K[b,h].  Rows with n_ctx = 0 get no
- * scores. */
+ * scores.  row_lse_opt: NULL, or the caller's row normalisers as in epicache_score_lse (single pass
+ * over K; causal_patch must then be 0). */
 EPICACHE_API int epicache_score_ragged(const epicache_params* params, const void* q, const void* k,
-                                       const int32_t* n_ctx, float* scores, void* workspace,
-                                       size_t workspace_bytes, void* hip_stream);
+                                       const int32_t* n_ctx, const float* row_lse_opt, float* scores,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Retention on given scores.  Writes keep (ascending within each head) and n_kept.  Score order and
  * per-head tie rule as epicache_topk. */
@@ -190,12 +191,13 @@ EPICACHE_API int epicache_compact_ragged(const epicache_params* params, int32_t 
                                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* score_ragged -> select_ragged -> compact_ragged on one stream.  n_kept is required: it is the
- * n_cached of each head for the next step (n_ctx_next = n_kept + next block).  scores_opt and
- * keep_idx_opt may be NULL. */
+ * n_cached of each head for the next step (n_ctx_next = n_kept + next block).  row_lse_opt as in
+ * epicache_score_ragged.  scores_opt and keep_idx_opt may be NULL. */
 EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32_t select, const void* q,
                                             void* k, void* v, const int32_t* n_ctx, const int32_t* budgets,
-                                            int32_t* n_kept, float* scores_opt, int32_t* keep_idx_opt,
-                                            void* workspace, size_t workspace_bytes, void* hip_stream);
+                                            const float* row_lse_opt, int32_t* n_kept, float* scores_opt,
+                                            int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
+                                            void* hip_stream);
 
 /* App. A.2 ("KeyDiff"): the attention-free baseline scorer, for the same epicache_topk /
  * epicache_compact (or *_ragged) back end.  Per (b, h): anchor = mean of the key states of the

@@ -93,10 +93,10 @@ def load() -> ctypes.CDLL:
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     i32c = ctypes.c_int32
     lib.epicache_ragged_workspace_size.argtypes = [pp, i32c, ctypes.POINTER(sz), ctypes.POINTER(i32c)]
-    lib.epicache_score_ragged.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_score_ragged.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_select_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
-    lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_score_keydiff.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_episode_medoids.argtypes = [vp, vp, i32c, i32c, i32c, vp, vp, vp]
     lib.epicache_match_queries.argtypes = [vp, vp, i32c, i32c, i32c, ctypes.c_float, vp, vp, vp]
@@ -200,9 +200,10 @@ def alloc_ragged_workspace(params: Params, select: int, device="cuda") -> torch.
                        device=device)
 
 
-def epicache_score_ragged(params: Params, q, k, n_ctx, scores, workspace) -> None:
-    _check(load().epicache_score_ragged(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(n_ctx), _ptr(scores),
-                                        _ptr(workspace), workspace.numel(), _stream()), "epicache_score_ragged")
+def epicache_score_ragged(params: Params, q, k, n_ctx, scores, workspace, row_lse=None) -> None:
+    _check(load().epicache_score_ragged(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(n_ctx), _ptr(row_lse),
+                                        _ptr(scores), _ptr(workspace), workspace.numel(), _stream()),
+           "epicache_score_ragged")
 
 
 def epicache_select_ragged(params: Params, select: int, scores, n_ctx, budgets, keep_idx, n_kept,
@@ -220,9 +221,9 @@ def epicache_compact_ragged(params: Params, select: int, keep_idx, n_kept, k, v,
 
 
 def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budgets, n_kept, workspace,
-                               scores=None, keep_idx=None) -> None:
+                               scores=None, keep_idx=None, row_lse=None) -> None:
     _check(load().epicache_evict_step_ragged(ctypes.byref(params), int(select), _ptr(q), _ptr(k), _ptr(v),
-                                             _ptr(n_ctx), _ptr(budgets), _ptr(n_kept), _ptr(scores),
+                                             _ptr(n_ctx), _ptr(budgets), _ptr(row_lse), _ptr(n_kept), _ptr(scores),
                                              _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step_ragged")
 

@@ -162,6 +162,18 @@ static int run_score(const Plan& pl, const void* q, const void* k, float* scores
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
+// Scoring with the caller's row normalisers: they take the place of pass 1 (one (max, sum) pair per row).
+static int run_score_lse(const Plan& pl, const void* q, const void* k, const float* row_lse, float* scores,
+                         char* ws, hipStream_t stream) {
+  Plan p1 = pl;
+  p1.n_splits = 1;
+  float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
+  if (launch_lse_to_stats(p1, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, true, stream)
+                             : launch_score_generic(p1, q, k, scores, stats, true, stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
 }  // namespace epicache
 
 using namespace epicache;
@@ -200,13 +212,7 @@ int epicache_score_lse(const epicache_params* params, const void* q, const void*
   if (misaligned(q) || misaligned(k) || misaligned(row_lse) || misaligned(scores) || misaligned(workspace))
     return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
-  pl.n_splits = 1;  // the caller's normalisers take the place of pass 1: one (max, sum) pair per row
-  hipStream_t stream = (hipStream_t)hip_stream;
-  float2* stats = reinterpret_cast<float2*>(static_cast<char*>(workspace) + pl.off_stats);
-  if (launch_lse_to_stats(pl, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
-  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, true, stream)
-                             : launch_score_generic(pl, q, k, scores, stats, true, stream);
-  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+  return run_score_lse(pl, q, k, row_lse, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
 }
 
 int epicache_score_keydiff(const epicache_params* params, const void* k, const int32_t* n_ctx_opt,
@@ -270,14 +276,7 @@ static int evict_step_impl(const epicache_params* params, const void* q, void* k
   float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
   int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
   auto score = [&]() -> int {
-    if (!with_lse) return run_score(pl, q, k, scores, ws, stream);
-    Plan p1 = pl;
-    p1.n_splits = 1;  // the caller's normalisers take the place of pass 1
-    float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
-    if (launch_lse_to_stats(p1, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
-    hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, true, stream)
-                               : launch_score_generic(p1, q, k, scores, stats, true, stream);
-    return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+    return with_lse ? run_score_lse(pl, q, k, row_lse, scores, ws, stream) : run_score(pl, q, k, scores, ws, stream);
   };
 
   if (pl.N <= pl.M) {  // nothing to evict: the cache is still filling up (App. A.3)
@@ -322,16 +321,21 @@ int epicache_ragged_workspace_size(const epicache_params* params, int32_t select
 }
 
 int epicache_score_ragged(const epicache_params* params, const void* q, const void* k, const int32_t* n_ctx,
-                          float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                          const float* row_lse_opt, float* scores, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
   Plan pl;
   int st = make_plan(params, &pl);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !n_ctx || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
-  if (misaligned(q) || misaligned(k) || misaligned(n_ctx) || misaligned(scores) || misaligned(workspace))
+  if (misaligned(q) || misaligned(k) || misaligned(n_ctx) || misaligned(row_lse_opt) || misaligned(scores) ||
+      misaligned(workspace))
     return EPICACHE_ERR_INVALID_ARG;
+  if (row_lse_opt && pl.causal_patch) return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < pl.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
   pl.n_ctx = n_ctx;
-  return run_score(pl, q, k, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  return row_lse_opt ? run_score_lse(pl, q, k, row_lse_opt, scores, ws, stream) : run_score(pl, q, k, scores, ws, stream);
 }
 
 int epicache_select_ragged(const epicache_params* params, int32_t select, const float* scores,
@@ -368,24 +372,25 @@ int epicache_compact_ragged(const epicache_params* params, int32_t select, const
 }
 
 int epicache_evict_step_ragged(const epicache_params* params, int32_t select, const void* q, void* k, void* v,
-                               const int32_t* n_ctx, const int32_t* budgets, int32_t* n_kept,
-                               float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                               const int32_t* n_ctx, const int32_t* budgets, const float* row_lse_opt,
+                               int32_t* n_kept, float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                                size_t workspace_bytes, void* hip_stream) {
   Plan pl;
   int st = make_ragged_plan(params, select, &pl);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !v || !n_ctx || !n_kept || !workspace) return EPICACHE_ERR_INVALID_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(n_ctx) || misaligned(budgets) ||
-      misaligned(n_kept) || misaligned(scores_opt) || misaligned(keep_idx_opt) || misaligned(workspace))
+      misaligned(row_lse_opt) || misaligned(n_kept) || misaligned(scores_opt) || misaligned(keep_idx_opt) ||
+      misaligned(workspace))
     return EPICACHE_ERR_INVALID_ARG;
-  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  if (k == v || (row_lse_opt && pl.causal_patch)) return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < pl.ws_total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
   char* ws = static_cast<char*>(workspace);
   hipStream_t stream = (hipStream_t)hip_stream;
   float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
   int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
   pl.n_ctx = n_ctx;
-  st = run_score(pl, q, k, scores, ws, stream);
+  st = row_lse_opt ? run_score_lse(pl, q, k, row_lse_opt, scores, ws, stream) : run_score(pl, q, k, scores, ws, stream);
   if (st != EPICACHE_OK) return st;
   if (launch_select_ragged(pl, select, scores, budgets, keep, n_kept, ws + pl.off_select, stream) != hipSuccess)
     return EPICACHE_ERR_DEVICE;

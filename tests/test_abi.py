@@ -116,20 +116,20 @@ def test_ragged_calls_validate_on_the_host():
     assert lib.epicache_ragged_workspace_size(ctypes.byref(prm), 2, ctypes.byref(sz), ctypes.byref(cap)) == \
         ep.ERR_INVALID_ARG                                                      # unknown selection rule
     assert lib.epicache_ragged_workspace_size(ctypes.byref(prm), 0, None, ctypes.byref(cap)) == ep.ERR_INVALID_ARG
-    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, None, a, a, need, None) == ep.ERR_INVALID_ARG
-    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, a, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, None, None, a, a, need, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_score_ragged(ctypes.byref(prm), a, a, a, None, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
     assert lib.epicache_select_ragged(ctypes.byref(prm), 1, a, a, None, a, None, a, need, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_select_ragged(ctypes.byref(prm), 1, a, a, None, a, a, a, need - 1, None) == \
         ep.ERR_WORKSPACE_TOO_SMALL
     assert lib.epicache_select_ragged(ctypes.byref(prm), 5, a, a, None, a, a, a, need, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_compact_ragged(ctypes.byref(prm), 0, a, a, a, a, None, 0, None) == ep.ERR_INVALID_ARG  # K is V
     assert lib.epicache_compact_ragged(ctypes.byref(prm), 0, a, None, a, b, None, 0, None) == ep.ERR_INVALID_ARG
-    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, None, None, None, a, need,
+    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, None, None, None, None, a, need,
                                           None) == ep.ERR_INVALID_ARG          # n_kept is required
-    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, a, None, None, a, need - 1,
+    assert lib.epicache_evict_step_ragged(ctypes.byref(prm), 1, a, a, b, a, None, None, a, None, None, a, need - 1,
                                           None) == ep.ERR_WORKSPACE_TOO_SMALL
     bad = _params(budget=0)
-    assert lib.epicache_evict_step_ragged(ctypes.byref(bad), 1, a, a, b, a, None, a, None, None, a, need,
+    assert lib.epicache_evict_step_ragged(ctypes.byref(bad), 1, a, a, b, a, None, None, a, None, None, a, need,
                                           None) == ep.ERR_INVALID_ARG
     # pooled selection keeps its per-head counters on chip: at most 1024 KV heads
     q = torch.empty(1, 2048, 1, 8, dtype=torch.float32)

@@ -103,6 +103,58 @@ def test_score_ragged_with_causal_patch_keys():
             assert (got[b, h, n:] == -7.0).all()
 
 
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_score_ragged_with_supplied_normalisers(reduce):
+    """row_lse given: single pass over K; every head's normaliser belongs to its own prefix of keys
+    (plus, for one batch item, extra mass as if the patch's own keys had been attended too)."""
+    from scipy.special import logsumexp
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=48)
+    n_max = 900
+    say(f"score_ragged row_lse reduce={reduce}")
+    q, k, _ = synth.make_layer(w, layer=2, n_ctx=n_max)
+    n_ctx = lengths(13, w.E, w.Hkv, n_max, (n_max, 1, 65))
+    qq, kk = pu.oracle_inputs(q, k)
+    G = w.Hq // w.Hkv
+    lse = np.empty((w.E, w.Hq, w.p), dtype=np.float64)
+    for b in range(w.E):
+        for hq in range(w.Hq):
+            n = n_ctx[b, hq // G]
+            z = (qq[b, hq] @ kk[b, hq // G, :n].T) / np.sqrt(w.d)
+            lse[b, hq] = logsumexp(z, axis=1) + (0.7 if b == 1 else 0.0)
+    qd, kd = q.to(DEV), k.to(DEV)
+    prm = ep.make_params(qd, kd, n_cached=0, n_block=n_max, budget=7, reduce=reduce)
+    ws = ep.alloc_workspace(prm)
+    scores = torch.full((w.E, w.Hkv, n_max), -7.0, dtype=torch.float32, device=DEV)
+    lse32 = torch.tensor(lse, dtype=torch.float32, device=DEV)
+    ep.epicache_score_ragged(prm, qd, kd, i32(n_ctx), scores, ws, row_lse=lse32)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy()
+    lse_used = lse32.cpu().numpy().astype(np.float64)      # the oracle gets the rounded values the GPU got
+    for b in range(w.E):
+        for h in range(w.Hkv):
+            n = n_ctx[b, h]
+            want = orc.score_given_lse(qq[b:b + 1, h * G:(h + 1) * G], kk[b:b + 1, h:h + 1], n,
+                                       lse_used[b:b + 1, h * G:(h + 1) * G], reduce)[0, 0]
+            pu.assert_scores_close(got[b, h, :n], want, pu.RTOL_BF16, f"b={b} h={h} n={n}")
+            assert (got[b, h, n:] == -7.0).all()
+    # whole ragged step on the same normalisers: same kept rows as the two-pass step where the
+    # normaliser is the plain one (batch item 0)
+    v = torch.randn(k.shape, generator=torch.Generator().manual_seed(1)).to(k.dtype)
+    outs = []
+    for use_lse in (False, True):
+        kd2, vd2 = k.to(DEV).clone(), v.to(DEV).clone()
+        prm2 = ep.make_params(qd, kd2, n_cached=0, n_block=n_max, budget=100, reduce=reduce)
+        ws2 = ep.alloc_ragged_workspace(prm2, ep.SELECT_POOLED)
+        n_kept = torch.zeros((w.E, w.Hkv), dtype=torch.int32, device=DEV)
+        ep.epicache_evict_step_ragged(prm2, ep.SELECT_POOLED, qd, kd2, vd2, i32(n_ctx), None, n_kept, ws2,
+                                      row_lse=lse32 if use_lse else None)
+        torch.cuda.synchronize()
+        outs.append((n_kept.cpu().numpy(), kd2.cpu()))
+    # same pool size; per head the two scorings may only trade tokens that sit on the threshold
+    assert outs[0][0][0].sum() == outs[1][0][0].sum()
+    assert np.abs(outs[0][0][0] - outs[1][0][0]).max() <= 2
+
+
 # ------------------------------------------------------------------- select
 
 def gpu_select(scores_np, n_ctx, budgets, m_max, select):
