@@ -45,6 +45,18 @@ typedef uint16_t bf16_t;  // raw storage
 __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+// The bare instructions: fmaxf() on values that went through pin() gets a canonicalising v_max x, x
+// in front of every operand, which doubled the ALU work of the max reduction.
+__device__ __forceinline__ float vmax(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 __device__ __forceinline__ void fence_sched() { __builtin_amdgcn_sched_barrier(0); }
 // Keeps the computation of x above this point: without it the optimiser sinks a slice of
 // arithmetic down to its first use, past the MFMAs it is meant to fill the shadow of.
@@ -192,8 +204,10 @@ __device__ __forceinline__ void stage_add(const float (&x)[16], float& s0, float
 template <int LO, int HI>
 __device__ __forceinline__ void stage_max(const float (&x)[16], float& s0, float& s1) {
 #pragma unroll
-  for (int v = LO; v < HI; v++) {
-    if (v & 1) s1 = fmaxf(s1, x[v]); else s0 = fmaxf(s0, x[v]);
+  for (int v = LO; v < HI; v += 2) {  // two values per instruction, alternating between the two chains
+    float& s = ((v - LO) & 2) ? s1 : s0;
+    if (v + 1 < HI) s = vmax3(s, x[v], x[v + 1]);
+    else s = vmax(s, x[v]);
   }
   if (HI > LO) pin(s0), pin(s1);
 }
@@ -441,13 +455,13 @@ template <int REDUCE>
 __device__ __forceinline__ float col_group(const f32x16& P, const float (&nl)[16], int g, float c2) {
   const float x0 = fmaf(P[4 * g + 0], c2, nl[4 * g + 0]), x1 = fmaf(P[4 * g + 1], c2, nl[4 * g + 1]);
   const float x2 = fmaf(P[4 * g + 2], c2, nl[4 * g + 2]), x3 = fmaf(P[4 * g + 3], c2, nl[4 * g + 3]);
-  if (REDUCE == EPICACHE_REDUCE_MAX) return fmaxf(max3(x0, x1, x2), x3);
+  if (REDUCE == EPICACHE_REDUCE_MAX) return vmax(vmax3(x0, x1, x2), x3);
   return (ex2(x0) + ex2(x1)) + (ex2(x2) + ex2(x3));
 }
 
 template <int REDUCE>
 __device__ __forceinline__ float col_merge(float col, float a, float b, float c, float d) {
-  if (REDUCE == EPICACHE_REDUCE_MAX) return max3(max3(a, b, c), d, col);
+  if (REDUCE == EPICACHE_REDUCE_MAX) return vmax3(vmax3(a, b, c), d, col);
   return col + ((a + b) + (c + d));
 }
 
@@ -497,7 +511,7 @@ __device__ __forceinline__ void reduce_unit(f32x16& acc, const bf16x8 (&a)[KS], 
   }
   if constexpr (REDUCE == EPICACHE_REDUCE_MAX) {
     stage_max<SL::reduce[KS - 1], SL::reduce[KS]>(x, s0, s1);
-    col = max3(col, s0, s1);
+    col = vmax3(col, s0, s1);
   } else {
     stage_exp<SL::reduce[KS - 1], SL::reduce[KS]>(x);
     stage_add<SL::reduce[KS - 2], SL::reduce[KS - 1]>(x, s0, s1);
