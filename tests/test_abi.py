@@ -66,6 +66,7 @@ def test_workspace_size_is_host_only_and_monotone():
     ("kv_stride_t", 132, ep.ERR_INVALID_ARG),    # not a multiple of 8
     ("kv_stride_h", 1000, ep.ERR_INVALID_ARG),   # capacity below N
     ("head_dim", 12, ep.ERR_UNSUPPORTED),
+    ("patch_len", 2048, ep.ERR_INVALID_ARG),     # the Q strides of the fixture do not hold 2048 rows per head
     ("kv_stride_t", 1 << 21, ep.ERR_UNSUPPORTED),  # token stride beyond the 32-bit row offsets of the kernels
     ("n_cached", (1 << 24) + 8, ep.ERR_INVALID_ARG),  # exceeds the capacity the strides imply
 ])
