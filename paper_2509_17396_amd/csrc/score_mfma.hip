@@ -300,7 +300,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
-  const int split = blockIdx.x, rb = blockIdx.y, bh = blockIdx.z;
+  // Workgroups are handed to the 8 XCDs round-robin by linear id.  The key splits (and row blocks) of one
+  // (b, h) read the same query rows, so they are given ids that land on one XCD and share its L2:
+  // id = xcd + 8 * (split + S * (rb + RB * (bh / 8))), bh % 8 = xcd.
+  const int n_rb = (pl.R + 32 * NQ * NW - 1) / (32 * NQ * NW);
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int split = within % pl.n_splits, rb = (within / pl.n_splits) % n_rb;
+  const int bh = (within / (pl.n_splits * n_rb)) * 8 + xcd;
+  if (bh >= pl.nb * pl.Hkv) return;
   const int b = bh / pl.Hkv, h = bh % pl.Hkv;
   const int row0 = rb * (32 * NQ * NW) + wave * (32 * NQ);
   const bool active = row0 < pl.R;  // waves without rows only help staging the key tiles
@@ -810,7 +817,9 @@ void launch_reduce_stream(const Plan& pl, const bf16_t* q, const bf16_t* k, cons
 template <int HD, int NQ, int NW>
 void launch_stats(const Plan& pl, const bf16_t* q, const bf16_t* k, float2* stats, hipStream_t stream) {
   const int rows_per_wg = 32 * NQ * NW;
-  dim3 grid(pl.n_splits, (pl.R + rows_per_wg - 1) / rows_per_wg, pl.nb * pl.Hkv);
+  const int n_rb = (pl.R + rows_per_wg - 1) / rows_per_wg;
+  const int bh8 = (pl.nb * pl.Hkv + 7) / 8 * 8;  // ids whose bh falls beyond the batch exit at once
+  dim3 grid((unsigned)(pl.n_splits * n_rb * bh8));
   hipLaunchKernelGGL((score_stats<HD, NQ, NW>), grid, dim3(NW * 64), 0, stream, q, k, stats, pl);
 }
 
