@@ -302,10 +302,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   const int l32 = lane & 31, hi = lane >> 5;
   // Workgroups are handed to the 8 XCDs round-robin by linear id.  The key splits (and row blocks) of one
   // (b, h) read the same query rows, so they are given ids that land on one XCD and share its L2:
-  // id = xcd + 8 * (split + S * (rb + RB * (bh / 8))), bh % 8 = xcd.
+  // id = xcd + 8 * (rb + RB * (split + S * (bh / 8))), bh % 8 = xcd.
   const int n_rb = (pl.R + 32 * NQ * NW - 1) / (32 * NQ * NW);
   const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
-  const int split = within % pl.n_splits, rb = (within / pl.n_splits) % n_rb;
+  const int rb = within % n_rb, split = (within / n_rb) % pl.n_splits;  // row blocks of a split side by side: one K fetch
   const int bh = (within / (pl.n_splits * n_rb)) * 8 + xcd;
   if (bh >= pl.nb * pl.Hkv) return;
   const int b = bh / pl.Hkv, h = bh % pl.Hkv;
@@ -549,10 +549,17 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hi = lane >> 5;
-  const int bh = blockIdx.y, b = bh / pl.Hkv, h = bh % pl.Hkv;
+  // XCD-aware ids as in pass 1: the key blocks of one (b, h) all stream the same query rows through LDS
+  // and are given ids that land on one XCD: id = xcd + 8 * (key block + NKB * (bh / 8)), bh % 8 = xcd.
+  const int n_kb = (pl.N + kKeysPerWG - 1) / kKeysPerWG;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int kb = within % n_kb;
+  const int bh = (within / n_kb) * 8 + xcd;
+  if (bh >= pl.nb * pl.Hkv) return;
+  const int b = bh / pl.Hkv, h = bh % pl.Hkv;
   const int N = ctx_rows(pl, bh);
-  if ((int)blockIdx.x * kKeysPerWG >= N) return;  // a shorter head of a ragged batch: no keys here
-  const int key0 = blockIdx.x * kKeysPerWG + wave * 64;
+  if (kb * kKeysPerWG >= N) return;  // a shorter head of a ragged batch: no keys here
+  const int key0 = kb * kKeysPerWG + wave * 64;
   const float c2 = pl.c2;
 
   using ST = Stager<HD, 4>;
@@ -845,7 +852,7 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
     }
     return hipGetLastError();
   }
-  dim3 g2((pl.N + kKeysPerWG - 1) / kKeysPerWG, nbh);
+  dim3 g2((unsigned)(((pl.N + kKeysPerWG - 1) / kKeysPerWG) * ((nbh + 7) / 8 * 8)));
   const size_t smem = 2 * TL::kTileBytes + (size_t)(pl.Rpad + 64) * sizeof(float);
   if (pl.reduce == EPICACHE_REDUCE_MAX)
     hipLaunchKernelGGL((score_reduce<HD, EPICACHE_REDUCE_MAX>), g2, dim3(256), smem, stream, q, k,
