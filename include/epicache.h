@@ -10,10 +10,12 @@
  * batch axis, all layers) are processed by one call.
  *
  * Conventions that hold for every entry point
- *   - `params` and `bytes_out` are HOST pointers.  Every other pointer is a
+ *   - `params`, `bytes_out`, `keep_capacity_out` and the arrays of
+ *     epicache_layer_budgets are HOST pointers.  Every other pointer is a
  *     DEVICE pointer, 16-byte aligned, owned by the caller.  The library never
  *     allocates, frees or retains device memory and keeps no state between
- *     calls.
+ *     calls, so it may be called from several host threads and its calls may
+ *     be captured into a HIP graph.
  *   - A call validates its arguments on the host, enqueues its kernels on
  *     `hip_stream` (a hipStream_t; NULL = the default stream) and returns
  *     without synchronising.  The return value is an epicache_status; it
