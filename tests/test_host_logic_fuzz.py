@@ -1,0 +1,85 @@
+"""Host-side logic under random parameters (no GPU): the validator never crashes, accepts every
+well-formed geometry inside the documented envelope, rejects what lies outside it with the documented
+status, and the workspace sizes it reports cover every buffer a step keeps there."""
+import ctypes
+
+import torch
+from hypothesis import given, settings, strategies as st
+
+from paper_2509_17396_amd import binding as ep
+
+
+def _dense_params(nb, Hkv, G, p, d, n_cached, n_block, budget, dtype, reduce, causal, extra_rows, pad):
+    Hq = Hkv * G
+    cap = n_cached + n_block + (p if causal else 0) + extra_rows
+    kst = d + 8 * pad
+    prm = ep.Params(ctypes.sizeof(ep.Params), nb, Hq, Hkv, d, n_cached, n_block, budget, p, dtype, reduce, 0.0,
+                    causal, 0, Hq * p * d, p * d, d, Hkv * cap * kst, cap * kst, kst)
+    return prm
+
+
+geometry = st.tuples(
+    st.integers(1, 6), st.integers(1, 8), st.integers(1, 7), st.integers(1, 300),
+    st.sampled_from([8, 16, 40, 64, 96, 128, 256]), st.integers(0, 5000), st.integers(0, 5000),
+    st.integers(1, 6000), st.sampled_from([ep.DTYPE_F32, ep.DTYPE_BF16]),
+    st.sampled_from([ep.REDUCE_MAX, ep.REDUCE_SUM]), st.integers(0, 1), st.integers(0, 50), st.integers(0, 3))
+
+
+@settings(max_examples=300, deadline=None)
+@given(geometry)
+def test_well_formed_geometries_are_accepted_and_sized(g):
+    nb, Hkv, G, p, d, n_cached, n_block, budget, dtype, reduce, causal, extra, pad = g
+    prm = _dense_params(*g)
+    lib = ep.load()
+    size = ctypes.c_size_t(0)
+    status = lib.epicache_workspace_size(ctypes.byref(prm), ctypes.byref(size))
+    N, R = n_cached + n_block, G * p
+    if N < 1:
+        assert status == ep.ERR_INVALID_ARG
+        return
+    if R > 8128:
+        assert status == ep.ERR_UNSUPPORTED
+        return
+    assert status == ep.OK, (g, status)
+    nbh = nb * Hkv
+    n_keep = min(budget, N)
+    # scores, kept indices and at least one (max, sum) pair per scoring row all live in the workspace
+    assert size.value >= nbh * N * 4 + nbh * n_keep * 4 + nbh * R * 8
+    assert size.value % 256 == 0
+    for select in (ep.SELECT_PER_HEAD, ep.SELECT_POOLED):
+        rsize, cap = ctypes.c_size_t(0), ctypes.c_int32(0)
+        assert lib.epicache_ragged_workspace_size(ctypes.byref(prm), select, ctypes.byref(rsize),
+                                                  ctypes.byref(cap)) == ep.OK
+        want_cap = min(N, budget if select == ep.SELECT_PER_HEAD else Hkv * budget)
+        assert cap.value == want_cap
+        assert rsize.value >= nbh * N * 4 + nbh * want_cap * 4 + nbh * 8
+
+
+@settings(max_examples=200, deadline=None)
+@given(geometry, st.sampled_from(["kv_stride_t", "kv_stride_h", "kv_stride_b", "q_stride_t", "q_stride_h",
+                                  "q_stride_b", "n_q_heads", "head_dim", "struct_size", "reserved"]),
+       st.integers(1, 7))
+def test_broken_geometries_are_rejected(g, field, delta):
+    nb, Hkv, G, p, d, n_cached, n_block = g[:7]
+    if n_cached + n_block < 1 or G * p > 8128:
+        return
+    prm = _dense_params(*g)
+    if field.endswith("stride_t") or field.endswith("stride_h") or field.endswith("stride_b"):
+        setattr(prm, field, getattr(prm, field) - delta)          # no longer a multiple of 8, or rows overlap
+        if field.endswith("_b") and nb == 1 and (getattr(prm, field) % 8 == 0):
+            return                                                 # the batch stride of a single item is not read
+    elif field == "n_q_heads":
+        if Hkv == 1:
+            return
+        prm.n_q_heads = prm.n_q_heads + (1 if (prm.n_q_heads + 1) % Hkv else 2) if Hkv > 2 else prm.n_q_heads + 1
+        if prm.n_q_heads % Hkv == 0:
+            return
+    elif field == "head_dim":
+        prm.head_dim = d + delta                                   # not a multiple of 8 (delta < 8)
+    elif field == "struct_size":
+        prm.struct_size = prm.struct_size - delta
+    elif field == "reserved":
+        prm.reserved = delta
+    size = ctypes.c_size_t(0)
+    status = ep.load().epicache_workspace_size(ctypes.byref(prm), ctypes.byref(size))
+    assert status in (ep.ERR_INVALID_ARG, ep.ERR_UNSUPPORTED), (g, field, delta, status)
