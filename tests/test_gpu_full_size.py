@@ -185,3 +185,31 @@ def test_config2_folded_ragged_step_as_benchmarked(select, pooled):
         got = [[keep[b, h, :int(n_kept[b, h])].cpu().numpy() for h in range(H)]]
         differ += pu.assert_ragged_keep_matches(got, rows_o, [int(budgets[b])], pooled, pu.RTOL_BF16, f"item {b}")
     say(f"  kept-set differences inside the band: {differ}; rows per head of item 0: {n_kept[0].tolist()}")
+
+
+def test_largest_batch_axis():
+    """n_batch * n_kv_heads at its documented maximum (65535 launches' worth of heads), both scoring paths:
+    properties over the whole batch on the device, sampled heads against the oracle."""
+    for dtype, d in ((torch.bfloat16, 64), (torch.float32, 16)):
+        nb, Hkv, G, p, N, M = 13107, 5, 2, 8, 70, 30          # 65535 (b, h) pairs
+        say(f"largest batch axis {dtype} d={d}")
+        gen = torch.Generator(device=DEV).manual_seed(11)
+        q = torch.randn((nb, Hkv * G, p, d), device=DEV, generator=gen).to(dtype)
+        k0 = torch.randn((nb, Hkv, N, d), device=DEV, generator=gen).to(dtype)
+        v0 = torch.randn((nb, Hkv, N, d), device=DEV, generator=gen).to(dtype)
+        k, v = k0.clone(), v0.clone()
+        scores, keep = evict_on_gpu(q, k, v, M, N, orc.REDUCE_SUM)
+        torch.testing.assert_close(scores.double().sum(dim=2),
+                                   torch.full((nb, Hkv), float(G * p), dtype=torch.float64, device=DEV),
+                                   rtol=1e-4, atol=0)
+        assert (keep[:, :, 1:] > keep[:, :, :-1]).all() and keep.min() >= 0 and keep.max() < N
+        idx = keep.long().unsqueeze(-1).expand(-1, -1, -1, d)
+        bits = torch.int16 if dtype == torch.bfloat16 else torch.int32
+        assert torch.equal(torch.gather(k0, 2, idx).view(bits), k[:, :, :M].view(bits))
+        assert torch.equal(torch.gather(v0, 2, idx).view(bits), v[:, :, :M].view(bits))
+        for (b, h) in ((0, 0), (nb - 1, Hkv - 1), (7001, 3)):
+            o = pu.oracle_score_one_head(q, k0, b, h, N, orc.REDUCE_SUM)
+            pu.assert_scores_close(scores[b, h].cpu().numpy(), o, pu.rtol_for(dtype), f"b={b} h={h}")
+            pu.assert_keep_matches(keep[b:b + 1, h:h + 1].cpu().numpy(), o[None, None], M, pu.rtol_for(dtype), f"b={b} h={h}")
+        del q, k0, v0, k, v, scores, keep, idx
+        torch.cuda.empty_cache()
