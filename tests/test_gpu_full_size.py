@@ -213,3 +213,25 @@ def test_largest_batch_axis():
             pu.assert_keep_matches(keep[b:b + 1, h:h + 1].cpu().numpy(), o[None, None], M, pu.rtol_for(dtype), f"b={b} h={h}")
         del q, k0, v0, k, v, scores, keep, idx
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 64), (torch.float32, 8)], ids=["bf16_mfma", "f32_generic"])
+def test_longest_context_one_head(dtype, d):
+    """N at its documented maximum (2^24 context rows) for a single head: the streaming selection (rows
+    re-read per radix digit) and 64-bit row offsets are exercised; the whole row is checked against the oracle."""
+    N, M, p = 1 << 24, 1_000_003, 4
+    say(f"longest context N={N} {dtype} d={d}")
+    gen = torch.Generator(device=DEV).manual_seed(3)
+    q = torch.randn((1, 1, p, d), device=DEV, generator=gen).to(dtype)
+    k0 = torch.randn((1, 1, N, d), device=DEV, generator=gen).to(dtype)
+    v0 = torch.randn((1, 1, N, d), device=DEV, generator=gen).to(dtype)
+    k, v = k0.clone(), v0.clone()
+    scores, keep = evict_on_gpu(q, k, v, M, N, orc.REDUCE_MAX)
+    o = pu.oracle_score_one_head(q, k0, 0, 0, N, orc.REDUCE_MAX)
+    pu.assert_scores_close(scores[0, 0].cpu().numpy(), o, pu.rtol_for(dtype), "longest")
+    differ = pu.assert_keep_matches(keep.cpu().numpy(), o[None, None], M, pu.rtol_for(dtype), "longest")
+    idx = keep.long().unsqueeze(-1).expand(-1, -1, -1, d)
+    bits = torch.int16 if dtype == torch.bfloat16 else torch.int32
+    assert torch.equal(torch.gather(k0, 2, idx).view(bits), k[:, :, :M].view(bits))
+    assert torch.equal(torch.gather(v0, 2, idx).view(bits), v[:, :, :M].view(bits))
+    say(f"  kept-set differences inside the band: {differ}")
