@@ -32,6 +32,30 @@ def test_library_exports_every_declared_symbol():
     assert re.fullmatch(r"\d+\.\d+\.\d+", ep.version())
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/epicache.h compiles as C99 and as C++ with warnings on, and the struct layout the ctypes
+    binding assumes is the one a C compiler produces."""
+    import subprocess
+    src = tmp_path / "abi_check.c"
+    src.write_text(
+        '#include <stddef.h>\n#include <stdio.h>\n#include "epicache.h"\n'
+        "int main(void) {\n"
+        "  epicache_params p; (void)p;\n"
+        '  printf("%zu %zu %zu\\n", sizeof(epicache_params), offsetof(epicache_params, q_stride_b),\n'
+        "         offsetof(epicache_params, causal_patch));\n"
+        "  return (int)(EPICACHE_SELECT_POOLED - 1 + EPICACHE_REDUCE_SUM - 1 + EPICACHE_DTYPE_BF16 - 1);\n"
+        "}\n")
+    inc = os.path.join(ROOT, "include")
+    exe = tmp_path / "abi_check"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe)],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(x) for x in out] == [ctypes.sizeof(ep.Params), ep.Params.q_stride_b.offset,
+                                     ep.Params.causal_patch.offset]
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc,
+                    str(src)], check=True)
+
+
 def test_params_struct_matches_header_layout():
     assert ctypes.sizeof(ep.Params) == 4 * 14 + 8 * 6
     assert ep.Params.q_stride_b.offset == 56
