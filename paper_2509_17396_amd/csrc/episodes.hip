@@ -42,74 +42,71 @@ constexpr int kNoIndex = 0x7fffffff;
 
 constexpr int kMedoidThreads = 1024;
 constexpr int kMedoidWaves = kMedoidThreads / 64;
-constexpr int kMaxDim = 8192;  // kMedoidThreads * 8 centroid accumulators per thread
+constexpr int kMaxDim = 8192;  // the centroid of a cluster is kept in LDS while its members are compared
+constexpr int kRowsInFlight = 32;
 
+// Centroids: workgroup (e, j) owns dims [256 j, 256 j + 256) of cluster e and sweeps the segments in index
+// order, 32 rows at a time.  Rows of other clusters are read too and multiplied by 0: no branch in the loop
+// and 32 independent loads in flight per thread (the sweep is latency-bound; splitting the dims over
+// workgroups multiplies the bytes in flight).
+__global__ __launch_bounds__(kThreads) void episode_centroids(const float* __restrict__ emb,
+                                                              const int32_t* __restrict__ assign, int K, int D,
+                                                              float* __restrict__ centroids) {
+  const int e = blockIdx.x, d = blockIdx.y * kThreads + threadIdx.x;
+  const bool own = d < D;
+  const float* col = emb + (own ? d : 0);
+  float acc = 0.f;
+  int count = 0;
+  for (int k0 = 0; k0 < K; k0 += kRowsInFlight) {
+    float x[kRowsInFlight], m[kRowsInFlight];
+#pragma unroll
+    for (int u = 0; u < kRowsInFlight; u++) {
+      const int k = k0 + u < K ? k0 + u : K - 1;
+      x[u] = col[(size_t)k * D];
+      const bool mine = k0 + u < K && assign[k] == e;
+      m[u] = mine ? 1.f : 0.f;
+      count += mine;
+    }
+#pragma unroll
+    for (int u = 0; u < kRowsInFlight; u++) acc = fmaf(m[u], x[u], acc);
+  }
+  if (own) centroids[(size_t)e * D + d] = count ? acc / (float)count : 0.f;
+}
+
+// Centroid-closest member of cluster e: the centroid (written by the kernel above) goes to LDS, the members
+// are dealt to the 16 waves round-robin, each wave keeps its best (cosine, index).
 __global__ __launch_bounds__(kMedoidThreads) void episode_medoids(const float* __restrict__ emb,
                                                                   const int32_t* __restrict__ assign, int K,
-                                                                  int D, float* __restrict__ centroids,
+                                                                  int D, const float* __restrict__ centroids,
                                                                   int32_t* __restrict__ medoid) {
   extern __shared__ float cent[];  // [D]
   __shared__ float sc[kMedoidWaves];
   __shared__ int si[kMedoidWaves];
   const int e = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // centroid: thread t owns dims t, t + 1024, ...; one sweep over the segments in index order.  Rows of
-  // other clusters are read too and multiplied by 0: no branch in the loop, eight loads in flight.
-  float acc[8];
-#pragma unroll
-  for (int j = 0; j < 8; j++) acc[j] = 0.f;
-  int count = 0;
-  for (int k0 = 0; k0 < K; k0 += 4) {
-    float m[4];
-#pragma unroll
-    for (int u = 0; u < 4; u++) {
-      const bool mine = k0 + u < K && assign[k0 + u] == e;
-      m[u] = mine ? 1.f : 0.f;
-      count += mine;
-    }
-    if (m[0] + m[1] + m[2] + m[3] == 0.f) continue;  // uniform across the workgroup
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-      const int d = tid + j * kMedoidThreads;
-      if (d < D) {
-        float x[4];
-#pragma unroll
-        for (int u = 0; u < 4; u++) x[u] = k0 + u < K ? emb[(size_t)(k0 + u) * D + d] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 4; u++) acc[j] = fmaf(m[u], x[u], acc[j]);
-      }
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 8; j++) {
-    const int d = tid + j * kMedoidThreads;
-    if (d < D) {
-      const float c = count ? acc[j] / (float)count : 0.f;
-      cent[d] = c;
-      centroids[(size_t)e * D + d] = c;
-    }
-  }
-  if (count == 0) {
-    if (tid == 0) medoid[e] = -1;
-    return;
-  }
+  for (int d = tid; d < D; d += kMedoidThreads) cent[d] = centroids[(size_t)e * D + d];
   __syncthreads();
   float csq = 0.f;
   for (int d = lane; d < D; d += 64) csq = fmaf(cent[d], cent[d], csq);
   csq = wave_sum(csq);
-  // members are dealt to the waves round-robin; each wave keeps its best (cosine, index)
   float best_c = -INFINITY;
   int best_i = kNoIndex, seen = 0;
-  for (int k = 0; k < K; k++) {
-    if (assign[k] != e) continue;
-    if ((seen++ % kMedoidWaves) != wave) continue;
-    float dot = 0.f, sq = 0.f;
-    for (int d = lane; d < D; d += 64) {
-      const float x = emb[(size_t)k * D + d];
-      dot = fmaf(x, cent[d], dot);
-      sq = fmaf(x, x, sq);
+  for (int k0 = 0; k0 < K; k0 += 64) {
+    // membership of 64 segments at a time: one coalesced load and a ballot instead of a dependent load per segment
+    const int kk = k0 + lane;
+    uint64_t members = __ballot(kk < K && assign[kk] == e);
+    while (members) {
+      const int k = k0 + __ffsll((unsigned long long)members) - 1;
+      members &= members - 1;
+      if ((seen++ % kMedoidWaves) != wave) continue;
+      float dot = 0.f, sq = 0.f;
+      for (int d = lane; d < D; d += 64) {
+        const float x = emb[(size_t)k * D + d];
+        dot = fmaf(x, cent[d], dot);
+        sq = fmaf(x, x, sq);
+      }
+      const float c = cosine_from(wave_sum(dot), wave_sum(sq), csq);
+      if (better(c, k, best_c, best_i)) best_c = c, best_i = k;
     }
-    const float c = cosine_from(wave_sum(dot), wave_sum(sq), csq);
-    if (better(c, k, best_c, best_i)) best_c = c, best_i = k;
   }
   if (lane == 0) sc[wave] = best_c, si[wave] = best_i;
   __syncthreads();
@@ -118,7 +115,7 @@ __global__ __launch_bounds__(kMedoidThreads) void episode_medoids(const float* _
     int i = si[0];
     for (int w = 1; w < kMedoidWaves; w++)
       if (better(sc[w], si[w], c, i)) c = sc[w], i = si[w];
-    medoid[e] = i;
+    medoid[e] = i == kNoIndex ? -1 : i;  // an empty cluster has no member
   }
 }
 
@@ -160,6 +157,8 @@ __global__ __launch_bounds__(kThreads) void match_queries(const float* __restric
 hipError_t launch_episode_medoids(const float* emb, const int32_t* assign, int K, int E, int D,
                                   float* centroids, int32_t* medoid, hipStream_t stream) {
   if (D > kMaxDim) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(episode_centroids, dim3(E, (D + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, emb,
+                     assign, K, D, centroids);
   hipLaunchKernelGGL(episode_medoids, dim3(E), dim3(kMedoidThreads), (size_t)D * sizeof(float), stream, emb,
                      assign, K, D, centroids, medoid);
   return hipGetLastError();
