@@ -30,7 +30,7 @@
  *     Strides are in elements and must be multiples of 8; K and V share strides.
  *     Query head hq belongs to KV head hq / (n_q_heads / n_kv_heads).
  *   - Supported: dtype f32 or bf16; head_dim a multiple of 8, 8..256;
- *     N <= 2^24; patch_len * (n_q_heads / n_kv_heads) <= 8128; n_batch * n_kv_heads <= 65535;
+ *     N <= 2^24; patch_len * (n_q_heads / n_kv_heads) <= 16384; n_batch * n_kv_heads <= 65535;
  *     token strides <= 2^20 elements.
  *     Anything else returns EPICACHE_ERR_UNSUPPORTED.
  *   - Calls that use the same workspace or the same K/V buffers must be ordered

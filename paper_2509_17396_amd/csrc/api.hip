@@ -80,7 +80,7 @@ int make_plan(const epicache_params* prm, Plan* out) {
   if (pl.d % 8 != 0 || pl.d < 8 || pl.d > 256) return EPICACHE_ERR_UNSUPPORTED;
   if (N64 > (1 << 24)) return EPICACHE_ERR_UNSUPPORTED;
   const int64_t R64 = (int64_t)pl.G * pl.p;
-  if (R64 > 8128) return EPICACHE_ERR_UNSUPPORTED;  // pass 2 keeps one normaliser per row in 64 KB of LDS, next to two tiles
+  if (R64 > 16384) return EPICACHE_ERR_UNSUPPORTED;  // pass 2 keeps one normaliser per row in LDS, next to two tiles
   const int64_t nbh = (int64_t)pl.nb * pl.Hkv;
   if (nbh > 65535) return EPICACHE_ERR_UNSUPPORTED;
 

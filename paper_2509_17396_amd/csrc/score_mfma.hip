@@ -854,13 +854,18 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
   }
   dim3 g2((unsigned)(((pl.N + kKeysPerWG - 1) / kKeysPerWG) * ((nbh + 7) / 8 * 8)));
   const size_t smem = 2 * TL::kTileBytes + (size_t)(pl.Rpad + 64) * sizeof(float);
-  if (pl.reduce == EPICACHE_REDUCE_MAX)
-    hipLaunchKernelGGL((score_reduce<HD, EPICACHE_REDUCE_MAX>), g2, dim3(256), smem, stream, q, k,
-                       stats, scores, pl);
-  else
-    hipLaunchKernelGGL((score_reduce<HD, EPICACHE_REDUCE_SUM>), g2, dim3(256), smem, stream, q, k,
-                       stats, scores, pl);
-  return hipGetLastError();
+  auto launch = [&](auto kernel) -> hipError_t {
+    if (smem > 64 * 1024) {
+      // very long patches: one normaliser per row no longer fits the default 64 KB of dynamic LDS
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, g2, dim3(256), smem, stream, q, k, stats, scores, pl);
+    return hipGetLastError();
+  };
+  if (pl.reduce == EPICACHE_REDUCE_MAX) return launch(score_reduce<HD, EPICACHE_REDUCE_MAX>);
+  return launch(score_reduce<HD, EPICACHE_REDUCE_SUM>);
 }
 
 }  // namespace

@@ -61,8 +61,10 @@ SCORE_CASES = [
     ("bf16_mfma_d64_R300", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=100, d=64), 450, None),
     ("bf16_mfma_huge_logits", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=16), 300, None),
     ("bf16_mfma_patch_as_long_as_a_block_R6144", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=2048), 200, None),
-    ("bf16_mfma_largest_R8128", "llama32_3b", dict(E=1, Hq=2, Hkv=1, p=4064), 70, None),
+    ("bf16_mfma_64KB_of_LDS_R8128", "llama32_3b", dict(E=1, Hq=2, Hkv=1, p=4064), 70, None),
     ("fp32_generic_R6000", "tiny", dict(E=1, Hq=4, Hkv=2, p=3000, d=16), 50, None),
+    ("bf16_mfma_G4_patch_2048_R8192", "llama31_8b", dict(E=1, Hq=4, Hkv=1, p=2048), 300, None),
+    ("bf16_mfma_largest_R16384", "llama31_8b", dict(E=1, Hq=4, Hkv=1, p=4096), 130, None),
 ]
 
 

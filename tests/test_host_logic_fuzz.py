@@ -37,7 +37,7 @@ def test_well_formed_geometries_are_accepted_and_sized(g):
     if N < 1:
         assert status == ep.ERR_INVALID_ARG
         return
-    if R > 8128:
+    if R > 16384:
         assert status == ep.ERR_UNSUPPORTED
         return
     assert status == ep.OK, (g, status)
@@ -61,7 +61,7 @@ def test_well_formed_geometries_are_accepted_and_sized(g):
        st.integers(1, 7))
 def test_broken_geometries_are_rejected(g, field, delta):
     nb, Hkv, G, p, d, n_cached, n_block = g[:7]
-    if n_cached + n_block < 1 or G * p > 8128:
+    if n_cached + n_block < 1 or G * p > 16384:
         return
     prm = _dense_params(*g)
     if field.endswith("stride_t") or field.endswith("stride_h") or field.endswith("stride_b"):
