@@ -435,3 +435,38 @@ def match_queries(queries, centroids, tau: float = -np.inf):
         cs[i] = best
         ep[i] = arg if best >= tau else -1
     return ep, cs
+
+
+# ---------------------------------------------------------------------------------------------
+# The patch's own attention output.  The patched prompt has to be run through the layer anyway
+# (Sec. 2.3: it is appended after the block and attends back to it), so the pass that produces the
+# softmax normalisers of Eq. 1 can also produce the patch tokens' attention output
+# O_t = sum_i Attn(x_t -> x_i) v_i.  Keys and values of the patch follow the context rows
+# (rows n_ctx .. n_ctx + p - 1); with causal_patch they are attended causally, without it the
+# softmax runs over the context rows only (the denominators score() uses).
+# ---------------------------------------------------------------------------------------------
+
+def patch_attention(q, k, v, n_ctx: int, causal_patch: bool = True, scale: float | None = None):
+    """Returns (O float64 [nb, Hq, p, d], lse float64 [nb, Hq, p]): attention output of every patch
+    query and the natural log of its softmax denominator."""
+    nb, Hq, p, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((nb, Hq, p, d), dtype=np.float64)
+    lse = np.empty((nb, Hq, p), dtype=np.float64)
+    for b in range(nb):
+        for hq in range(Hq):
+            h = hq // G
+            for t in range(p):
+                n_keys = n_ctx + (t + 1 if causal_patch else 0)
+                keys = np.asarray(k[b, h, :n_keys], dtype=np.float64)
+                vals = np.asarray(v[b, h, :n_keys], dtype=np.float64)
+                z = scale * (keys @ np.asarray(q[b, hq, t], dtype=np.float64))
+                m = z.max()
+                e = np.exp(z - m)
+                s = e.sum()
+                out[b, hq, t] = (e / s) @ vals
+                lse[b, hq, t] = m + math.log(s)
+    return out, lse
