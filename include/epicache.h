@@ -201,6 +201,19 @@ EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32
                                             int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
                                             void* hip_stream);
 
+/* Sec. 2.3: the patched prompt's own pass through the attention layer.  For every patch query t of every
+ * query head: out[b,hq,t,:] = sum_i softmax_i(scale * q.k_i) V[b,h,i,:] and lse_out[b,hq,t] = natural log of
+ * sum_i exp(scale * q.k_i), over the N context rows and, with causal_patch = 1, the patch rows 0..t that
+ * follow them (rows N .. N+patch_len-1 of K and V).  lse_out is exactly the row_lse that epicache_score_lse /
+ * epicache_evict_step_lse take (call those with causal_patch = 0), so this call plus
+ * epicache_evict_step_lse is the patch's attention, Eq. 1 scoring, selection and compaction with K read twice.
+ * In: q, k, v (read only; V has the strides of K).  Out: out [n_batch, n_q_heads, patch_len, head_dim]
+ * in the dtype of the inputs, dense; lse_out [n_batch, n_q_heads, patch_len] float32, dense.
+ * bf16 with head_dim 128 runs on the matrix cores (weights rounded to bf16 before the product with V, fp32
+ * accumulation); other dtypes / head dims take a plain fp32 kernel.  No workspace. */
+EPICACHE_API int epicache_patch_attention(const epicache_params* params, const void* q, const void* k,
+                                          const void* v, void* out, float* lse_out, void* hip_stream);
+
 /* App. A.2 ("KeyDiff"): the attention-free baseline scorer, for the same epicache_topk /
  * epicache_compact (or *_ragged) back end.  Per (b, h): anchor = mean of the key states of the
  * context rows; scores[b,h,i] = -cos(K[b,h,i,:], anchor), so the keys that point away from the bulk

@@ -215,6 +215,20 @@ int epicache_score_lse(const epicache_params* params, const void* q, const void*
   return run_score_lse(pl, q, k, row_lse, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
 }
 
+int epicache_patch_attention(const epicache_params* params, const void* q, const void* k, const void* v,
+                             void* out, float* lse_out, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !out || !lse_out) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse_out))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return EPICACHE_ERR_INVALID_ARG;
+  if ((int64_t)pl.nb * pl.Hq * pl.p > INT32_MAX) return EPICACHE_ERR_UNSUPPORTED;
+  hipError_t e = launch_patch_attention(pl, q, k, v, out, lse_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
 int epicache_score_keydiff(const epicache_params* params, const void* k, const int32_t* n_ctx_opt,
                            float* scores, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Plan pl;

@@ -71,6 +71,9 @@ hipError_t launch_score_keydiff(const Plan& pl, const void* k, float* scores, vo
 hipError_t launch_select_ragged(const Plan& pl, int select, const float* scores, const int32_t* budgets,
                                 int32_t* keep, int32_t* n_kept, void* records, hipStream_t stream);
 
+// Attention output and log-sum-exp of the patch queries (dense out [nb, Hq, p, d], lse [nb, Hq, p]).
+hipError_t launch_patch_attention(const Plan& pl, const void* q, const void* k, const void* v, void* out,
+                                  float* lse, hipStream_t stream);
 // Episode geometry on fp32 embeddings: cluster centroids + centroid-closest members, query matching.
 hipError_t launch_episode_medoids(const float* emb, const int32_t* assign, int K, int E, int D,
                                   float* centroids, int32_t* medoid, hipStream_t stream);

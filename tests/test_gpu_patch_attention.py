@@ -1,0 +1,99 @@
+"""GPU parity of the patch attention output and normalisers against the CPU oracle, and of the chain
+patch attention -> scoring on the returned normalisers against the oracle's causal-patch scores."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import epicache_oracle as orc
+from paper_2509_17396_amd import binding as ep
+from paper_2509_17396_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def wl(name, **kw):
+    return synth.WORKLOADS[name].scaled(**kw)
+
+
+def gpu_patch_attention(q, k, v, N, causal):
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    prm = ep.make_params(qd, kd, n_cached=0, n_block=N, budget=1, causal_patch=causal)
+    out = torch.full(qd.shape, float("nan"), dtype=qd.dtype, device=DEV)
+    lse = torch.full(qd.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    ep.epicache_patch_attention(prm, qd, kd, vd, out, lse)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), lse
+
+
+def out_tolerance(o64, v64, dtype):
+    """Elementwise bound.  The output is a convex combination of value rows, so its error is absolute, in
+    units of the largest value.  fp32 path: accumulation order only.  bf16 path: the output itself is rounded
+    to bf16 (half an ulp, 2^-9 relative, doubled for slack) and the weights are rounded to bf16 before the
+    product with V (2^-9 relative each, so at most 2^-9 of the largest value in total)."""
+    vmax = np.abs(v64).max()
+    if dtype == torch.float32:
+        return 1e-5 * vmax + 0 * o64
+    return 2.0 ** -8 * np.abs(o64) + 2.0 ** -9 * vmax
+
+
+CASES = [
+    # name, base workload, overrides, context rows N
+    ("fp32_plain_d40", "tiny", dict(E=2, Hq=6, Hkv=2, p=5, d=40), 203),
+    ("fp32_plain_long_patch", "tiny", dict(E=1, Hq=2, Hkv=1, p=150, d=16), 300),
+    ("bf16_plain_d64", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=20, d=64), 333),
+    ("bf16_mfma_R192_three_waves", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=64), 640),
+    ("bf16_mfma_R128_four_waves", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=64), 500),
+    ("bf16_mfma_R64_two_waves", "llama32_3b", dict(E=1, Hq=2, Hkv=2, p=64), 257),
+    ("bf16_mfma_ragged_rows_p37", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=37), 1000),
+    ("bf16_mfma_two_patch_tiles_p100", "llama31_8b", dict(E=1, Hq=8, Hkv=2, p=100), 777),
+    ("bf16_mfma_one_context_key", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=16), 1),
+    ("bf16_mfma_student_t", "stress", dict(E=1, Hq=8, Hkv=2, p=32), 1500),
+]
+
+
+@pytest.mark.parametrize("causal", [1, 0], ids=["causal_patch", "context_only"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_patch_attention_matches_oracle(case, causal):
+    name, base, over, N = case
+    w = wl(base, **over)
+    say(f"patch_attention {name} causal={causal}")
+    q, k, v = synth.make_layer(w, layer=2, n_ctx=N + w.p)
+    out, lse, _ = gpu_patch_attention(q, k, v, N, causal)
+    qq, kk = pu.oracle_inputs(q, k)
+    vv = synth.to_f64_numpy(v)
+    o_out, o_lse = orc.patch_attention(qq, kk, vv, N, bool(causal))
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    err_lse = np.abs(lse - o_lse).max()
+    tol = out_tolerance(o_out, vv[:, :, :N + w.p], q.dtype)
+    ratio = (np.abs(out - o_out) / tol).max()
+    assert err_lse <= 2e-5 * (1 + np.abs(o_lse).max()), f"{name}: lse err {err_lse:.3e}"
+    assert ratio <= 1.0, f"{name}: output error {ratio:.2f} x its bound"
+    say(f"  max |lse err| {err_lse:.2e}, max |out err| {np.abs(out - o_out).max():.2e} = {ratio:.2f} x the bound")
+
+
+def test_patch_attention_then_scoring_on_its_normalisers():
+    """The normalisers the attention pass returns feed the single-pass scoring: together they give the
+    causal-patch scores of Eq. 1 with K read twice."""
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=64)
+    N = 900
+    say("patch_attention -> score_lse")
+    q, k, v = synth.make_layer(w, layer=4, n_ctx=N + w.p)
+    _, _, lse_dev = gpu_patch_attention(q, k, v, N, 1)
+    qd, kd = q.to(DEV), k.to(DEV)
+    for reduce in (orc.REDUCE_MAX, orc.REDUCE_SUM):
+        prm = ep.make_params(qd, kd, n_cached=0, n_block=N, budget=7, reduce=reduce)
+        ws = ep.alloc_workspace(prm)
+        scores = torch.empty((w.E, w.Hkv, N), dtype=torch.float32, device=DEV)
+        ep.epicache_score_lse(prm, qd, kd, lse_dev, scores, ws)
+        torch.cuda.synchronize()
+        want = orc.score_causal_patch(*pu.oracle_inputs(q, k), N, reduce)
+        pu.assert_scores_close(scores.cpu().numpy(), want, pu.RTOL_BF16, f"reduce={reduce}")
