@@ -66,6 +66,14 @@ __device__ __forceinline__ bf16x8 read_vt_frag(const unsigned char* vtile, int k
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// max(x[l], x[l ^ 32]) in every lane, on the vector ALU: the swap leaves the lower half's values in both
+// halves of one register and the upper half's in both halves of the other.
+__device__ __forceinline__ float max_across_halves(float x) {
+  const unsigned int u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return vmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void patch_attention_mfma(const bf16_t* __restrict__ q,
                                                                    const bf16_t* __restrict__ k,
@@ -142,12 +150,20 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void patch_attention_mf
     if (active) {
       const int first = t * kKeyTile;
       const bool plain = first + kKeyTile <= N;  // every key of the tile is a context key: no masking
+      bf16x8 kf[KS];
+      read_frags<kHD>(kf, ktile, 0, l32, hi);
 #pragma unroll
       for (int ks = 0; ks < 2; ks++) {
-        bf16x8 kf[KS];
-        read_frags<kHD>(kf, ktile, ks, l32, hi);
         f32x16 sacc;
         mfma_chain<KS>(sacc, kf, qf);
+        // LDS reads that the arithmetic below can hide: the key fragments of the second half and the eight
+        // V^T fragments of this half
+        if (ks == 0) read_frags<kHD>(kf, ktile, 1, l32, hi);
+        bf16x8 vf[4][2];
+#pragma unroll
+        for (int d = 0; d < 4; d++)
+#pragma unroll
+          for (int st = 0; st < 2; st++) vf[d][st] = read_vt_frag(vtile, ks, st, d, lane);
         if (!plain) {
 #pragma unroll
           for (int i = 0; i < 16; i++) {
@@ -160,8 +176,7 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void patch_attention_mf
         const float a0 = vmax3(sacc[0], sacc[1], sacc[2]), a1 = vmax3(sacc[3], sacc[4], sacc[5]);
         const float a2 = vmax3(sacc[6], sacc[7], sacc[8]), a3 = vmax3(sacc[9], sacc[10], sacc[11]);
         const float a4 = vmax3(sacc[12], sacc[13], sacc[14]);
-        float mn = vmax3(vmax3(a0, a1, a2), vmax3(a3, a4, sacc[15]), m);
-        mn = fmaxf(mn, __shfl_xor(mn, 32));
+        const float mn = max_across_halves(vmax3(vmax3(a0, a1, a2), vmax3(a3, a4, sacc[15]), m));
         if (__any(mn > m)) {  // some row of the wave has a new maximum: bring sums and outputs to the new reference
           const float corr = ex2((m - mn) * c2);
           l *= corr;
@@ -191,13 +206,10 @@ __global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void patch_attention_mf
           pf[st] = __builtin_bit_cast(bf16x8, packed);
         }
 #pragma unroll
-        for (int d = 0; d < 4; d++) {
+        for (int st = 0; st < 2; st++)
 #pragma unroll
-          for (int st = 0; st < 2; st++) {
-            const bf16x8 vf = read_vt_frag(vtile, ks, st, d, lane);
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st], o[d], 0, 0, 0);
-          }
-        }
+          for (int d = 0; d < 4; d++)  // four independent accumulators back to back
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[d][st], pf[st], o[d], 0, 0, 0);
       }
     }
     wait_vmem();
@@ -304,13 +316,9 @@ void launch_mfma(const Plan& pl, const void* q, const void* k, const void* v, vo
 hipError_t launch_patch_attention(const Plan& pl, const void* q, const void* k, const void* v, void* out,
                                   float* lse, hipStream_t stream) {
   if (pl.dtype == EPICACHE_DTYPE_BF16 && pl.d == kHD) {
-    // waves per workgroup (32 rows each): whichever of 2, 3, 4 pads R least, the larger on a tie
-    int best = 4;
-    for (int nw = 3; nw >= 2; nw--) {
-      const int pad_best = (pl.R + 32 * best - 1) / (32 * best) * 32 * best;
-      const int pad_nw = (pl.R + 32 * nw - 1) / (32 * nw) * 32 * nw;
-      if (pad_nw < pad_best) best = nw;
-    }
+    // waves per workgroup (32 rows each).  Two workgroups fit a CU (64 KB of LDS each), so four waves per
+    // workgroup give the 2 waves per SIMD the registers allow; fewer only when R itself is smaller.
+    const int best = pl.R <= 64 ? 2 : pl.R <= 96 ? 3 : 4;
     if (best == 4) launch_mfma<4>(pl, q, k, v, out, lse, stream);
     else if (best == 3) launch_mfma<3>(pl, q, k, v, out, lse, stream);
     else launch_mfma<2>(pl, q, k, v, out, lse, stream);

@@ -175,6 +175,10 @@ def test_keydiff_and_episode_calls_validate_on_the_host():
     assert lib.epicache_score_keydiff(ctypes.byref(prm), a, None, a, a, 16, None) == ep.ERR_WORKSPACE_TOO_SMALL
     assert lib.epicache_score_keydiff(ctypes.byref(prm), a, ctypes.c_void_p(4100), a, a, need, None) == \
         ep.ERR_INVALID_ARG
+    b = ctypes.c_void_p(8192)
+    assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, None, a, None) == ep.ERR_INVALID_ARG
+    assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, a, b, None) == ep.ERR_INVALID_ARG   # out is q
+    assert lib.epicache_patch_attention(ctypes.byref(_params(budget=0)), a, a, a, b, b, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_episode_medoids(a, a, 10, 0, 8, a, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_episode_medoids(a, None, 10, 2, 8, a, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_episode_medoids(a, a, 10, 2, 10000, a, a, None) == ep.ERR_UNSUPPORTED
