@@ -214,6 +214,16 @@ EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32
 EPICACHE_API int epicache_patch_attention(const epicache_params* params, const void* q, const void* k,
                                           const void* v, void* out, float* lse_out, void* hip_stream);
 
+/* Alg. 1 phase A3 with the patch's forward pass folded in: epicache_patch_attention (out as documented there;
+ * the normalisers stay in the workspace) followed by the single-pass scoring on those normalisers, the
+ * top-M selection and the in-place compaction, on one stream.  With causal_patch = 1 the denominators are the
+ * model's own (context keys and the patch's causal keys, rows N .. N+patch_len-1 of K and V, which are never
+ * scored or kept); with 0 they are those of epicache_evict_step.  K is read twice, V once before it is
+ * compacted.  scores_opt / keep_idx_opt and the N <= budget case as in epicache_evict_step. */
+EPICACHE_API int epicache_evict_step_attn(const epicache_params* params, const void* q, void* k, void* v,
+                                          void* out, float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream);
+
 /* App. A.2 ("KeyDiff"): the attention-free baseline scorer, for the same epicache_topk /
  * epicache_compact (or *_ragged) back end.  Per (b, h): anchor = mean of the key states of the
  * context rows; scores[b,h,i] = -cos(K[b,h,i,:], anchor), so the keys that point away from the bulk

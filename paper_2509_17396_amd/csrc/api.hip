@@ -120,6 +120,8 @@ int make_plan(const epicache_params* prm, Plan* out) {
   off += align256((size_t)nbh * pl.N * sizeof(float));
   pl.off_keep = off;
   off += align256((size_t)nbh * pl.n_keep * sizeof(int32_t));
+  pl.off_lse = off;  // row normalisers of the attention-fused step
+  off += align256((size_t)pl.nb * pl.Hq * pl.p * sizeof(float));
   pl.ws_total = off;
   const size_t keydiff = align256(keydiff_workspace_bytes(pl));
   if (pl.ws_total < keydiff) pl.ws_total = keydiff;
@@ -145,6 +147,8 @@ static int make_ragged_plan(const epicache_params* prm, int32_t select, Plan* ou
   }
   size_t off = pl.off_keep;
   off += align256((size_t)nbh * pl.keep_stride * sizeof(int32_t));
+  pl.off_lse = off;
+  off += align256((size_t)pl.nb * pl.Hq * pl.p * sizeof(float));
   pl.off_select = off;
   off += align256(select_ragged_record_bytes(pl));
   if (pl.ws_total < off) pl.ws_total = off;
@@ -227,6 +231,45 @@ int epicache_patch_attention(const epicache_params* params, const void* q, const
   if ((int64_t)pl.nb * pl.Hq * pl.p > INT32_MAX) return EPICACHE_ERR_UNSUPPORTED;
   hipError_t e = launch_patch_attention(pl, q, k, v, out, lse_out, (hipStream_t)hip_stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+int epicache_evict_step_attn(const epicache_params* params, const void* q, void* k, void* v, void* out,
+                             float* scores_opt, int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !out || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace) ||
+      misaligned(scores_opt) || misaligned(keep_idx_opt))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v || out == q || out == k || out == v) return EPICACHE_ERR_INVALID_ARG;
+  if ((int64_t)pl.nb * pl.Hq * pl.p > INT32_MAX) return EPICACHE_ERR_UNSUPPORTED;
+  if (workspace_bytes < pl.ws_total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* lse = reinterpret_cast<float*>(ws + pl.off_lse);
+  // the patch's pass through the layer: its output, and the normaliser of every scoring row ...
+  if (launch_patch_attention(pl, q, k, v, out, lse, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  // ... which already fix the denominator (context keys, plus the patch's own with causal_patch), so the
+  // scoring needs one pass over the context keys
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + pl.off_scores);
+  int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + pl.off_keep);
+  Plan ps = pl;
+  ps.causal_patch = 0;
+  if (pl.N <= pl.M) {  // nothing to evict
+    if (scores_opt) {
+      st = run_score_lse(ps, q, k, lse, scores, ws, stream);
+      if (st != EPICACHE_OK) return st;
+    }
+    if (keep_idx_opt && launch_iota_keep(pl, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  }
+  st = run_score_lse(ps, q, k, lse, scores, ws, stream);
+  if (st != EPICACHE_OK) return st;
+  if (launch_topk(pl, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  if (launch_compact(pl, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
 }
 
 int epicache_score_keydiff(const epicache_params* params, const void* k, const int32_t* n_ctx_opt,

@@ -31,7 +31,7 @@ struct Plan {
   int reduce_splits;  // key splits of the streaming reduction pass
   int reduce_tiles_per_split;
   // workspace layout (byte offsets, 256-aligned)
-  size_t off_stats, off_scores, off_keep, ws_total;
+  size_t off_stats, off_scores, off_keep, off_lse, ws_total;
   // ragged batches: device arrays indexed by b * Hkv + h, null in the uniform calls
   const int32_t* n_ctx;   // context rows per (b, h), at most N; N is then the pitch of a score row
   const int32_t* n_kept;  // rows kept per (b, h), read by the compaction

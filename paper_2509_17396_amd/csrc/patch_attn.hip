@@ -74,8 +74,13 @@ __device__ __forceinline__ float max_across_halves(float x) {
   return vmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Built for one wave per SIMD (no cap of 256 registers per wave).  Capped at 256 registers the same source
+// produced outputs that differed from run to run in the last bf16 bit of ~10 % of the elements (always within
+// the parity tolerance): the allocator then reuses the registers of MFMA operands for LDS loads issued right
+// behind the MFMA, and the outcome depended on timing.  Uncapped, every configuration tested is bit-identical
+// from run to run, which tests/test_gpu_patch_attention.py checks.
 template <int NW>
-__global__ __launch_bounds__(NW * 64, (NW >= 4 ? 2 : 1)) void patch_attention_mfma(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(NW * 64, 1) void patch_attention_mfma(const bf16_t* __restrict__ q,
                                                                    const bf16_t* __restrict__ k,
                                                                    const bf16_t* __restrict__ v,
                                                                    bf16_t* __restrict__ out,
@@ -316,8 +321,8 @@ void launch_mfma(const Plan& pl, const void* q, const void* k, const void* v, vo
 hipError_t launch_patch_attention(const Plan& pl, const void* q, const void* k, const void* v, void* out,
                                   float* lse, hipStream_t stream) {
   if (pl.dtype == EPICACHE_DTYPE_BF16 && pl.d == kHD) {
-    // waves per workgroup (32 rows each).  Two workgroups fit a CU (64 KB of LDS each), so four waves per
-    // workgroup give the 2 waves per SIMD the registers allow; fewer only when R itself is smaller.
+    // waves per workgroup (32 rows each): four unless R itself is smaller, so that K and V tiles are
+    // re-read by as few row blocks as possible
     const int best = pl.R <= 64 ? 2 : pl.R <= 96 ? 3 : 4;
     if (best == 4) launch_mfma<4>(pl, q, k, v, out, lse, stream);
     else if (best == 3) launch_mfma<3>(pl, q, k, v, out, lse, stream);

@@ -179,6 +179,15 @@ def test_keydiff_and_episode_calls_validate_on_the_host():
     assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, None, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, a, b, None) == ep.ERR_INVALID_ARG   # out is q
     assert lib.epicache_patch_attention(ctypes.byref(_params(budget=0)), a, a, a, b, b, None) == ep.ERR_INVALID_ARG
+    c, d = ctypes.c_void_p(12288), ctypes.c_void_p(16384)
+    step = lib.epicache_evict_step_attn
+    assert step(ctypes.byref(prm), a, b, c, None, None, None, d, need, None) == ep.ERR_INVALID_ARG     # no out
+    assert step(ctypes.byref(prm), a, b, b, d, None, None, d, need, None) == ep.ERR_INVALID_ARG        # k is v
+    assert step(ctypes.byref(prm), a, b, c, b, None, None, d, need, None) == ep.ERR_INVALID_ARG        # out is k
+    assert step(ctypes.byref(prm), a, b, c, ctypes.c_void_p(20480), None, None, d, 16, None) == \
+        ep.ERR_WORKSPACE_TOO_SMALL
+    assert step(ctypes.byref(prm), a, b, c, ctypes.c_void_p(20484), None, None, d, need, None) == \
+        ep.ERR_INVALID_ARG                                                                             # alignment
     assert lib.epicache_episode_medoids(a, a, 10, 0, 8, a, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_episode_medoids(a, None, 10, 2, 8, a, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_episode_medoids(a, a, 10, 2, 10000, a, a, None) == ep.ERR_UNSUPPORTED

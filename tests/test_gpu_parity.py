@@ -461,3 +461,15 @@ def test_evict_step_lse_equals_evict_step_up_to_the_band(reduce):
     pu.assert_keep_matches(keep_np, o_scores, w.M, pu.RTOL_BF16, "evict_step_lse")
     np.testing.assert_array_equal(synth.raw_bits_numpy(kd.cpu())[:, :, :w.M], orc.compact(kb, keep_np))
     np.testing.assert_array_equal(synth.raw_bits_numpy(vd.cpu())[:, :, :w.M], orc.compact(vb, keep_np))
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_scores_are_bit_identical_from_run_to_run(reduce):
+    """No atomics and a fixed reduction order: the same inputs give the same bits (both pass-2 forms)."""
+    for base, over, N in (("llama32_3b", dict(E=4, Hq=6, Hkv=2, p=64), 2048), ("llama31_8b", dict(E=2, Hq=8, Hkv=2, p=100), 1500)):
+        w = wl(base, **over)
+        q, k, _ = synth.make_layer(w, layer=0, n_ctx=N)
+        qd, kd = q.to(DEV), k.to(DEV)
+        first = gpu_score(qd, kd, N, w.M, reduce)
+        for _ in range(3):
+            assert np.array_equal(gpu_score(qd, kd, N, w.M, reduce).view(np.uint32), first.view(np.uint32))

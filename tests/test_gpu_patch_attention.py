@@ -97,3 +97,65 @@ def test_patch_attention_then_scoring_on_its_normalisers():
         torch.cuda.synchronize()
         want = orc.score_causal_patch(*pu.oracle_inputs(q, k), N, reduce)
         pu.assert_scores_close(scores.cpu().numpy(), want, pu.RTOL_BF16, f"reduce={reduce}")
+
+
+@pytest.mark.parametrize("causal", [1, 0], ids=["causal_patch", "context_only"])
+def test_evict_step_with_the_patch_attention_folded_in(causal):
+    """epicache_evict_step_attn: the patch's attention output, then scoring on its normalisers, selection and
+    compaction.  Output against the oracle's attention, kept rows against the oracle's scores under the same
+    denominator (within the band), cache = bit-exact gather, and identical to the two separate calls."""
+    w = wl("llama32_3b", E=2, Hq=6, Hkv=2, p=64, M=384, B=256)
+    N = w.M + w.B
+    say(f"evict_step_attn causal={causal}")
+    q, k, v = synth.make_layer(w, layer=6, n_ctx=N + w.p)
+    qd, kd, vd = q.to(DEV), k.to(DEV).clone(), v.to(DEV).clone()
+    prm = ep.make_params(qd, kd, n_cached=w.M, n_block=w.B, budget=w.M, reduce=orc.REDUCE_MAX, causal_patch=causal)
+    ws = ep.alloc_workspace(prm)
+    out = torch.full(qd.shape, float("nan"), dtype=qd.dtype, device=DEV)
+    scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+    keep = torch.full((w.E, w.Hkv, w.M), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step_attn(prm, qd, kd, vd, out, ws, scores, keep)
+    torch.cuda.synchronize()
+    qq, kk = pu.oracle_inputs(q, k)
+    vv = synth.to_f64_numpy(v)
+    o_out, _ = orc.patch_attention(qq, kk, vv, N, bool(causal))
+    tol = out_tolerance(o_out, vv[:, :, :N + w.p], q.dtype)
+    assert (np.abs(out.float().cpu().numpy() - o_out) <= tol).all()
+    o_scores = orc.score_causal_patch(qq, kk, N, orc.REDUCE_MAX) if causal else orc.score(qq, kk, N, orc.REDUCE_MAX)
+    pu.assert_scores_close(scores.cpu().numpy(), o_scores, pu.RTOL_BF16, "scores")
+    keep_np = keep.cpu().numpy()
+    differ = pu.assert_keep_matches(keep_np, o_scores, w.M, pu.RTOL_BF16, "keep")
+    kb, vb = synth.raw_bits_numpy(k), synth.raw_bits_numpy(v)
+    np.testing.assert_array_equal(synth.raw_bits_numpy(kd.cpu())[:, :, :w.M], orc.compact(kb, keep_np))
+    np.testing.assert_array_equal(synth.raw_bits_numpy(vd.cpu())[:, :, :w.M], orc.compact(vb, keep_np))
+    # the same through the two separate calls
+    kd2, vd2 = k.to(DEV).clone(), v.to(DEV).clone()
+    out2 = torch.empty_like(out)
+    lse2 = torch.empty(qd.shape[:3], dtype=torch.float32, device=DEV)
+    ep.epicache_patch_attention(prm, qd, kd2, vd2, out2, lse2)
+    prm0 = ep.make_params(qd, kd2, n_cached=w.M, n_block=w.B, budget=w.M, reduce=orc.REDUCE_MAX)
+    ep.epicache_evict_step_lse(prm0, qd, kd2, vd2, lse2, ep.alloc_workspace(prm0))
+    torch.cuda.synchronize()
+    assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
+    assert torch.equal(kd2.view(torch.int16), kd.view(torch.int16)) and torch.equal(vd2.view(torch.int16), vd.view(torch.int16))
+    say(f"  tokens differing inside the band: {differ}")
+
+
+def test_patch_attention_is_bit_identical_from_run_to_run():
+    """Same inputs, same bits, for every workgroup shape the launcher picks (R = 64, 96, 128, 192, 256)."""
+    for Hq, p in ((2, 64), (2, 96), (4, 64), (6, 64), (8, 64)):
+        w = wl("llama32_3b", E=2, Hq=Hq, Hkv=2, p=p, M=384, B=256)
+        N = w.M + w.B
+        q, k, v = synth.make_layer(w, layer=6, n_ctx=N + w.p)
+        qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+        prm = ep.make_params(qd, kd, n_cached=w.M, n_block=w.B, budget=w.M, causal_patch=1)
+        runs = []
+        for _ in range(4):
+            out = torch.empty_like(qd)
+            lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=DEV)
+            ep.epicache_patch_attention(prm, qd, kd, vd, out, lse)
+            torch.cuda.synchronize()
+            runs.append((out, lse))
+        for out, lse in runs[1:]:
+            assert torch.equal(out.view(torch.int16), runs[0][0].view(torch.int16)), f"R={w.R}: output differs between runs"
+            assert torch.equal(lse.view(torch.int32), runs[0][1].view(torch.int32)), f"R={w.R}: lse differs between runs"
