@@ -17,7 +17,11 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(b
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 // The bare instructions: fmaxf() on values that went through pin() gets a canonicalising v_max x, x
-// in front of every operand, which doubled the ALU work of the max reduction.
+// in front of every operand, which doubled the ALU work of the max reduction.  The compiler's hazard pass does
+// not see inline assembly as a vector ALU instruction and inserts no wait states for it: these must never be
+// the first reader of an MFMA result (12 wait states after an 8-pass MFMA on gfx950) or of a transcendental's
+// result.  The callers read values that a compiler-visible instruction has already read or produced;
+// tests/test_isa_hazards.py checks the generated ISA for it.
 __device__ __forceinline__ float vmax(float a, float b) {
   float r;
   asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));

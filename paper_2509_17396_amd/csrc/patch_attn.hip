@@ -71,16 +71,18 @@ __device__ __forceinline__ bf16x8 read_vt_frag(const unsigned char* vtile, int k
 __device__ __forceinline__ float max_across_halves(float x) {
   const unsigned int u = __float_as_uint(x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return vmax(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// Built for one wave per SIMD (no cap of 256 registers per wave).  Capped at 256 registers the same source
-// produced outputs that differed from run to run in the last bf16 bit of ~10 % of the elements (always within
-// the parity tolerance): the allocator then reuses the registers of MFMA operands for LDS loads issued right
-// behind the MFMA, and the outcome depended on timing.  Uncapped, every configuration tested is bit-identical
-// from run to run, which tests/test_gpu_patch_attention.py checks.
+// The row maximum is taken with compiler-visible max operations, not the hand-written v_max3_f32 of the scoring
+// kernels: the compiler's hazard pass does not treat inline assembly as a vector ALU instruction, so a
+// hand-written v_max3_f32 scheduled straight behind the S chain read the accumulators before the matrix core
+// had written them (no wait states inserted).  The stale maximum is still a valid reference, so results stayed
+// inside the tolerance but differed from run to run in the last bf16 bit.
+// Two waves per SIMD (a cap of 256 registers per wave) when a workgroup has 3 or 4 waves; the 2-wave form keeps
+// the uncapped allocation.
 template <int NW>
-__global__ __launch_bounds__(NW * 64, 1) void patch_attention_mfma(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma(const bf16_t* __restrict__ q,
                                                                    const bf16_t* __restrict__ k,
                                                                    const bf16_t* __restrict__ v,
                                                                    bf16_t* __restrict__ out,
@@ -178,10 +180,10 @@ __global__ __launch_bounds__(NW * 64, 1) void patch_attention_mfma(const bf16_t*
           }
         }
         // row maximum over this lane's 16 keys, then over the two lanes of the row
-        const float a0 = vmax3(sacc[0], sacc[1], sacc[2]), a1 = vmax3(sacc[3], sacc[4], sacc[5]);
-        const float a2 = vmax3(sacc[6], sacc[7], sacc[8]), a3 = vmax3(sacc[9], sacc[10], sacc[11]);
-        const float a4 = vmax3(sacc[12], sacc[13], sacc[14]);
-        const float mn = max_across_halves(vmax3(vmax3(a0, a1, a2), vmax3(a3, a4, sacc[15]), m));
+        const float a0 = max3(sacc[0], sacc[1], sacc[2]), a1 = max3(sacc[3], sacc[4], sacc[5]);
+        const float a2 = max3(sacc[6], sacc[7], sacc[8]), a3 = max3(sacc[9], sacc[10], sacc[11]);
+        const float a4 = max3(sacc[12], sacc[13], sacc[14]);
+        const float mn = max_across_halves(max3(max3(a0, a1, a2), max3(a3, a4, sacc[15]), m));
         if (__any(mn > m)) {  // some row of the wave has a new maximum: bring sums and outputs to the new reference
           const float corr = ex2((m - mn) * c2);
           l *= corr;
