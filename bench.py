@@ -199,6 +199,34 @@ def main():
     torch.cuda.synchronize()
     t_attn = sum(e[0].elapsed_time(e[1]) for e in ev6) / len(ev6) * 1e-3
 
+    # ---- the step with the patch's forward pass folded in (attention output, then scoring on its
+    # normalisers, selection, compaction) in one call
+    ev7 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.stage_reps)]
+    for rep in range(args.stage_reps + 1):
+        kp.copy_(kfresh), vp.copy_(vfresh)
+        e = ev7[rep - 1] if rep > 0 else [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        ep.epicache_evict_step_attn(prm, q0, kp, vp, attn_out, ws)
+        e[1].record()
+    torch.cuda.synchronize()
+    t_step_attn = sum(e[0].elapsed_time(e[1]) for e in ev7) / len(ev7) * 1e-3
+
+    # ---- the other reduction over the scoring rows (Eq. 1 takes the maximum; the headline line is quoted on
+    # the column sum): same data flow, timed beside it
+    other = ep.REDUCE_MAX if reduce == ep.REDUCE_SUM else ep.REDUCE_SUM
+    prm_other = ep.make_params(q0, k0, n_cached=w.M, n_block=w.B, budget=w.M, reduce=other)
+    ev8 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.stage_reps)]
+    for rep in range(args.stage_reps + 1):
+        kp.copy_(kfresh), vp.copy_(vfresh)
+        e = ev8[rep - 1] if rep > 0 else [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        ep.epicache_score(prm_other, q0, kp, scores, ws)
+        e[1].record()
+        ep.epicache_evict_step(prm_other, q0, kp, vp, ws)
+        e[2].record()
+    torch.cuda.synchronize()
+    t_score_other, t_step_other = (sum(e[i].elapsed_time(e[i + 1]) for e in ev8) / len(ev8) * 1e-3 for i in range(2))
+
     # ---- the attention-free KeyDiff scorer on the same K (second workload of the same back end)
     ev4 = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.stage_reps)]
     for rep in range(args.stage_reps + 1):
@@ -250,6 +278,13 @@ def main():
                             "frac_mfma_peak": 2 * flops_score / t_attn / 1e12 / PEAK_BF16_MFMA_TFLOPS,
                             "note": "epicache_patch_attention (Q.K^T and P.V, K and V read once); its normalisers "
                                     "feed score_given_lse; not part of the timed step"},
+        "evict_step_attn": {"ms": t_step_attn * 1e3,
+                            "note": "epicache_evict_step_attn: patch_attention + score_given_lse + topk + compact in one "
+                                    "call; not part of the timed step"},
+        "other_reduce": {"reduce": "max" if other == ep.REDUCE_MAX else "sum", "score_ms": t_score_other * 1e3,
+                         "evict_step_ms": t_step_other * 1e3,
+                         "tokens_per_s": tokens_per_step / t_step_other,
+                         "note": "the same step with the other reduction over the scoring rows, HIP events around one call"},
         "score_keydiff": {"ms": t_keydiff * 1e3, "gbs": (nbh * w.N * (w.d * 2.0 + 4.0)) / t_keydiff / 1e9,
                           "frac_hbm_peak": (nbh * w.N * (w.d * 2.0 + 4.0)) / t_keydiff / 1e9 / PEAK_HBM_GBS,
                           "note": "epicache_score_keydiff: K read once + scores written as algorithmic bytes "
