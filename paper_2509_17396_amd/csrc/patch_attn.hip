@@ -14,6 +14,8 @@
 // Anything else (fp32 inputs, other head dims): a plain fp32 kernel.
 #include <hip/hip_bf16.h>
 
+#include <type_traits>
+
 #include "mfma_tiles.h"
 
 namespace epicache {
@@ -24,6 +26,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kHD = 128;
+constexpr float kLazyBits = 8.f;
 using TL = Tile<kHD>;
 
 // V tiles use their own swizzle: 16-byte chunk c of key row r sits at position c ^ (4 * (r % 4)), so the four
@@ -102,8 +105,11 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
   const int bh = (within / n_rb) * 8 + xcd;
   if (bh >= pl.nb * pl.Hkv) return;
   const int b = bh / pl.Hkv, h = bh % pl.Hkv;
-  const int row0 = rb * (32 * NW) + wave * 32;
-  const bool active = row0 < pl.R;  // waves without rows only help staging the tiles
+  // the 32-row blocks are dealt evenly to the n_rb workgroups of a head: workgroups that do the same amount of
+  // work stream K and V at the same pace, so the second one finds the tiles in the XCD's L2
+  const int blocks_per_rb = ((pl.R + 31) / 32 + n_rb - 1) / n_rb;
+  const int row0 = (rb * blocks_per_rb + wave) * 32;
+  const bool active = wave < blocks_per_rb && row0 < pl.R;  // waves without rows only help staging the tiles
   const float c2 = pl.c2;
   const int N = pl.N;
   const int n_keys = N + (pl.causal_patch ? pl.p : 0);  // context rows, then the patch's own rows
@@ -144,16 +150,19 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
   for (int d = 0; d < 4; d++)
 #pragma unroll
     for (int i = 0; i < 16; i++) o[d][i] = 0.f;
+  const float lazy = kLazyBits / c2;  // in units of the raw dot product
   float m = kNoMax, l = 0.f;  // running row maximum (raw dot products, shared by lanes l and l^32) and this lane's sum
 
   stage(0, 0);
   wait_vmem();
   __syncthreads();
-  int buf = 0;
-  for (int t = 0; t < tiles; t++) {
-    const unsigned char* ktile = lds_k + buf * TL::kTileBytes;
-    const unsigned char* vtile = lds_v + buf * TL::kTileBytes;
-    if (t + 1 < tiles) stage(buf ^ 1, t + 1);
+  // One 64-key tile out of buffer BUF.  The buffer index is a compile-time constant (the tile loop below is
+  // unrolled by two) so that every LDS address is a loop-invariant lane offset plus an immediate.
+  auto tile_step = [&](auto buf_c, int t) {
+    constexpr int BUF = decltype(buf_c)::value;
+    const unsigned char* ktile = lds_k + BUF * TL::kTileBytes;
+    const unsigned char* vtile = lds_v + BUF * TL::kTileBytes;
+    if (t + 1 < tiles) stage(BUF ^ 1, t + 1);
     if (active) {
       const int first = t * kKeyTile;
       const bool plain = first + kKeyTile <= N;  // every key of the tile is a context key: no masking
@@ -184,7 +193,11 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
         const float a2 = max3(sacc[6], sacc[7], sacc[8]), a3 = max3(sacc[9], sacc[10], sacc[11]);
         const float a4 = max3(sacc[12], sacc[13], sacc[14]);
         const float mn = max_across_halves(max3(max3(a0, a1, a2), max3(a3, a4, sacc[15]), m));
-        if (__any(mn > m)) {  // some row of the wave has a new maximum: bring sums and outputs to the new reference
+        // The reference m only has to keep the exponentials in range, so it follows the maximum lazily: sums
+        // and outputs move to a new reference only when some row's maximum exceeds the current one by more than
+        // 2^kLazyBits in weight (weights then stay below that factor; fp32 sums and bf16 weights keep their
+        // relative precision).  Without the slack ~60 % of the 32-key steps of a 4096-key context rescale.
+        if (__any(mn > m + lazy)) {
           const float corr = ex2((m - mn) * c2);
           l *= corr;
 #pragma unroll
@@ -221,7 +234,10 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
     }
     wait_vmem();
     __syncthreads();
-    buf ^= 1;
+  };
+  for (int t = 0; t < tiles; t += 2) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < tiles) tile_step(std::integral_constant<int, 1>{}, t + 1);
   }
 
   if (!active) return;
