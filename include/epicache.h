@@ -214,6 +214,16 @@ EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32
 EPICACHE_API int epicache_patch_attention(const epicache_params* params, const void* q, const void* k,
                                           const void* v, void* out, float* lse_out, void* hip_stream);
 
+/* Sec. 2.3 on caches whose heads hold different numbers of tokens (head-wise non-uniform retention,
+ * App. A.2): epicache_patch_attention with the context length of head (b, h) read from
+ * n_ctx[b * n_kv_heads + h] (device memory, int32, clamped to [0, n_cached + n_block]); with
+ * causal_patch = 1 the patch rows of that head follow its own context (rows n_ctx .. n_ctx + patch_len - 1).
+ * A query without a single key (empty context, causal_patch = 0) gets out = 0 and lse_out = -inf.
+ * lse_out is what epicache_score_ragged / epicache_evict_step_ragged take as row_lse_opt. */
+EPICACHE_API int epicache_patch_attention_ragged(const epicache_params* params, const void* q, const void* k,
+                                                 const void* v, const int32_t* n_ctx, void* out, float* lse_out,
+                                                 void* hip_stream);
+
 /* Alg. 1 phase A3 with the patch's forward pass folded in: epicache_patch_attention (out as documented there;
  * the normalisers stay in the workspace) followed by the single-pass scoring on those normalisers, the
  * top-M selection and the in-place compaction, on one stream.  With causal_patch = 1 the denominators are the

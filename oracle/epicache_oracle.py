@@ -446,21 +446,30 @@ def match_queries(queries, centroids, tau: float = -np.inf):
 # softmax runs over the context rows only (the denominators score() uses).
 # ---------------------------------------------------------------------------------------------
 
-def patch_attention(q, k, v, n_ctx: int, causal_patch: bool = True, scale: float | None = None):
+def patch_attention(q, k, v, n_ctx, causal_patch: bool = True, scale: float | None = None):
     """Returns (O float64 [nb, Hq, p, d], lse float64 [nb, Hq, p]): attention output of every patch
-    query and the natural log of its softmax denominator."""
+    query and the natural log of its softmax denominator.
+    n_ctx: one context length for all heads, or an integer array [nb, Hkv] for caches whose heads hold
+    different numbers of tokens (head-wise non-uniform retention, App. A.2): head (b, h) then has its
+    context in rows 0 .. n_ctx[b,h]-1 and the patch's keys and values right behind them.  A query with no
+    key at all (empty context, no causal patch keys) gets O = 0 and lse = -inf."""
     nb, Hq, p, d = q.shape
     Hkv = k.shape[1]
     G = Hq // Hkv
     if scale is None:
         scale = 1.0 / math.sqrt(d)
-    out = np.empty((nb, Hq, p, d), dtype=np.float64)
+    lengths = np.broadcast_to(np.asarray(n_ctx, dtype=np.int64), (nb, Hkv))
+    out = np.empty((nb, Hq, p, np.shape(v)[-1]), dtype=np.float64)   # value rows may be wider than d
     lse = np.empty((nb, Hq, p), dtype=np.float64)
     for b in range(nb):
         for hq in range(Hq):
             h = hq // G
             for t in range(p):
-                n_keys = n_ctx + (t + 1 if causal_patch else 0)
+                n_keys = int(lengths[b, h]) + (t + 1 if causal_patch else 0)
+                if n_keys == 0:
+                    out[b, hq, t] = 0.0
+                    lse[b, hq, t] = -np.inf
+                    continue
                 keys = np.asarray(k[b, h, :n_keys], dtype=np.float64)
                 vals = np.asarray(v[b, h, :n_keys], dtype=np.float64)
                 z = scale * (keys @ np.asarray(q[b, hq, t], dtype=np.float64))

@@ -26,6 +26,7 @@ ENTRY_POINTS = (
     "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
     "epicache_evict_step_ragged", "epicache_score_keydiff", "epicache_patch_attention",
+    "epicache_patch_attention_ragged",
     "epicache_evict_step_attn",
     "epicache_episode_medoids", "epicache_match_queries", "epicache_status_string", "epicache_version",
 )
@@ -100,6 +101,7 @@ def load() -> ctypes.CDLL:
     lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_score_keydiff.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_patch_attention.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+    lib.epicache_patch_attention_ragged.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
     lib.epicache_evict_step_attn.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_episode_medoids.argtypes = [vp, vp, i32c, i32c, i32c, vp, vp, vp]
     lib.epicache_match_queries.argtypes = [vp, vp, i32c, i32c, i32c, ctypes.c_float, vp, vp, vp]
@@ -234,6 +236,12 @@ def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budg
 def epicache_patch_attention(params: Params, q, k, v, out, lse_out) -> None:
     _check(load().epicache_patch_attention(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse_out),
                                            _stream()), "epicache_patch_attention")
+
+
+def epicache_patch_attention_ragged(params: Params, q, k, v, n_ctx, out, lse_out) -> None:
+    _check(load().epicache_patch_attention_ragged(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(n_ctx),
+                                                  _ptr(out), _ptr(lse_out), _stream()),
+           "epicache_patch_attention_ragged")
 
 
 def epicache_evict_step_attn(params: Params, q, k, v, out, workspace, scores=None, keep_idx=None) -> None:

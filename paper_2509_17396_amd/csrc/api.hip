@@ -233,6 +233,21 @@ int epicache_patch_attention(const epicache_params* params, const void* q, const
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
+int epicache_patch_attention_ragged(const epicache_params* params, const void* q, const void* k, const void* v,
+                                    const int32_t* n_ctx, void* out, float* lse_out, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !n_ctx || !out || !lse_out) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(n_ctx) || misaligned(out) || misaligned(lse_out))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return EPICACHE_ERR_INVALID_ARG;
+  if ((int64_t)pl.nb * pl.Hq * pl.p > INT32_MAX) return EPICACHE_ERR_UNSUPPORTED;
+  pl.n_ctx = n_ctx;
+  hipError_t e = launch_patch_attention(pl, q, k, v, out, lse_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
 int epicache_evict_step_attn(const epicache_params* params, const void* q, void* k, void* v, void* out,
                              float* scores_opt, int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
                              void* hip_stream) {

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
   const int row0 = (rb * blocks_per_rb + wave) * 32;
   const bool active = wave < blocks_per_rb && row0 < pl.R;  // waves without rows only help staging the tiles
   const float c2 = pl.c2;
-  const int N = pl.N;
+  const int N = ctx_rows(pl, bh);  // this head's own context length in a ragged batch
   const int n_keys = N + (pl.causal_patch ? pl.p : 0);  // context rows, then the patch's own rows
   const int tiles = (n_keys + kKeyTile - 1) / kKeyTile;
 
@@ -119,6 +119,17 @@ __global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma
   const bool row_ok = r < pl.R;
   const int rr = row_ok ? r : 0;
   const int t_row = rr % pl.p;         // patch token index: sees patch keys 0..t_row
+  if (n_keys == 0) {  // a head without a single key (workgroup-uniform): O = 0, lse = -inf
+    if (active && row_ok) {
+      const int hq = h * pl.G + r / pl.p;
+      const size_t orow = ((size_t)b * pl.Hq + hq) * pl.p + t_row;
+      if (hi == 0) lse_out[orow] = -INFINITY;
+      uint4* o4 = reinterpret_cast<uint4*>(out + orow * kHD + hi * 64);
+#pragma unroll
+      for (int j = 0; j < 8; j++) o4[j] = make_uint4(0, 0, 0, 0);
+    }
+    return;
+  }
   bf16x8 qf[KS];
   {
     const bf16_t* qrow = q + b * pl.qsb + (int64_t)(h * pl.G + rr / pl.p) * pl.qsh + (int64_t)t_row * pl.qst + hi * 8;
@@ -283,7 +294,7 @@ __global__ __launch_bounds__(256) void patch_attention_plain(const T* __restrict
   __syncthreads();
   const T* kbase = k + b * pl.ksb + (int64_t)h * pl.ksh;
   const T* vbase = v + b * pl.ksb + (int64_t)h * pl.ksh;
-  const int n_keys = pl.N + (pl.causal_patch ? t + 1 : 0);
+  const int n_keys = ctx_rows(pl, b * pl.Hkv + h) + (pl.causal_patch ? t + 1 : 0);
   float m = -INFINITY, l = 0.f, acc = 0.f;  // acc: column tid of the output, relative to the reference m
   auto block_reduce = [&](float x, bool is_max) {
     for (int off = 32; off >= 1; off >>= 1) {
@@ -320,8 +331,8 @@ __global__ __launch_bounds__(256) void patch_attention_plain(const T* __restrict
     __syncthreads();  // w[] is rewritten by the next chunk
   }
   const size_t orow = ((size_t)b * pl.Hq + hq) * pl.p + t;
-  if (tid < pl.d) from_f32(out[orow * pl.d + tid], acc / l);
-  if (tid == 0) lse_out[orow] = (m + log2f(l)) * 0.69314718055994530942f;
+  if (tid < pl.d) from_f32(out[orow * pl.d + tid], n_keys > 0 ? acc / l : 0.f);  // no key at all: O = 0, lse = -inf
+  if (tid == 0) lse_out[orow] = n_keys > 0 ? (m + log2f(l)) * 0.69314718055994530942f : -INFINITY;
 }
 
 template <int NW>

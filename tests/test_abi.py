@@ -179,6 +179,10 @@ def test_keydiff_and_episode_calls_validate_on_the_host():
     assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, None, a, None) == ep.ERR_INVALID_ARG
     assert lib.epicache_patch_attention(ctypes.byref(prm), a, a, a, a, b, None) == ep.ERR_INVALID_ARG   # out is q
     assert lib.epicache_patch_attention(ctypes.byref(_params(budget=0)), a, a, a, b, b, None) == ep.ERR_INVALID_ARG
+    ragged = lib.epicache_patch_attention_ragged
+    assert ragged(ctypes.byref(prm), a, a, a, None, b, b, None) == ep.ERR_INVALID_ARG                   # no lengths
+    assert ragged(ctypes.byref(prm), a, a, a, ctypes.c_void_p(4100), b, b, None) == ep.ERR_INVALID_ARG  # alignment
+    assert ragged(ctypes.byref(prm), a, a, a, a, a, b, None) == ep.ERR_INVALID_ARG                      # out is q
     c, d = ctypes.c_void_p(12288), ctypes.c_void_p(16384)
     step = lib.epicache_evict_step_attn
     assert step(ctypes.byref(prm), a, b, c, None, None, None, d, need, None) == ep.ERR_INVALID_ARG     # no out

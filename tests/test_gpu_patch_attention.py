@@ -159,3 +159,90 @@ def test_patch_attention_is_bit_identical_from_run_to_run():
         for out, lse in runs[1:]:
             assert torch.equal(out.view(torch.int16), runs[0][0].view(torch.int16)), f"R={w.R}: output differs between runs"
             assert torch.equal(lse.view(torch.int32), runs[0][1].view(torch.int32)), f"R={w.R}: lse differs between runs"
+
+
+RAGGED_CASES = [
+    # name, base workload, overrides, longest context, per-(b, h) lengths (None = drawn)
+    ("bf16_mfma", "llama32_3b", dict(E=3, Hq=6, Hkv=2, p=64), 700, [[700, 0], [1, 333], [64, 65]]),
+    ("bf16_mfma_drawn", "llama31_8b", dict(E=4, Hq=8, Hkv=4, p=37), 1500, None),
+    ("fp32_plain", "tiny", dict(E=2, Hq=4, Hkv=2, p=9, d=24), 260, [[0, 260], [17, 256]]),
+]
+
+
+@pytest.mark.parametrize("causal", [1, 0], ids=["causal_patch", "context_only"])
+@pytest.mark.parametrize("case", RAGGED_CASES, ids=[c[0] for c in RAGGED_CASES])
+def test_ragged_patch_attention_matches_oracle(case, causal):
+    """Every head with its own context length (read from device memory); the patch rows of a head follow its
+    own context.  Rows no head may touch hold NaN on the GPU side."""
+    name, base, over, n_max, lengths = case
+    w = wl(base, **over)
+    say(f"patch_attention_ragged {name} causal={causal}")
+    if lengths is None:
+        lengths = np.random.default_rng(5).integers(0, n_max + 1, size=(w.E, w.Hkv))
+        lengths[0, 0], lengths[-1, -1] = n_max, 0
+    n = np.asarray(lengths, dtype=np.int64)
+    q, k, v = synth.make_layer(w, layer=3, n_ctx=n_max + w.p)
+    k_dev, v_dev = k.clone(), v.clone()
+    for b in range(w.E):
+        for h in range(w.Hkv):
+            k_dev[b, h, n[b, h] + (w.p if causal else 0):] = float("nan")
+            v_dev[b, h, n[b, h] + (w.p if causal else 0):] = float("nan")
+    qd, kd, vd = q.to(DEV), k_dev.to(DEV), v_dev.to(DEV)
+    nd = torch.tensor(n, dtype=torch.int32, device=DEV)
+    prm = ep.make_params(qd, kd, n_cached=0, n_block=n_max, budget=1, causal_patch=causal)
+    out = torch.full(qd.shape, float("nan"), dtype=qd.dtype, device=DEV)
+    lse = torch.full(qd.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    ep.epicache_patch_attention_ragged(prm, qd, kd, vd, nd, out, lse)
+    torch.cuda.synchronize()
+    out, lse = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    qq, kk = pu.oracle_inputs(q, k)
+    vv = synth.to_f64_numpy(v)
+    o_out, o_lse = orc.patch_attention(qq, kk, vv, n, bool(causal))
+    assert not np.isnan(out).any() and not np.isnan(lse).any()
+    G = w.Hq // w.Hkv
+    empty = np.repeat(n == 0, G, axis=1) & (not causal)           # [E, Hq]: queries without any key
+    assert (lse[empty] == -np.inf).all() and (out[empty] == 0).all() and (o_lse[empty] == -np.inf).all()
+    live = ~empty
+    err_lse = np.abs(lse[live] - o_lse[live]).max()
+    tol = out_tolerance(o_out, vv, q.dtype)
+    ratio = (np.abs(out - o_out) / tol)[live].max()
+    assert err_lse <= 2e-5 * (1 + np.abs(o_lse[live]).max()), f"{name}: lse err {err_lse:.3e}"
+    assert ratio <= 1.0, f"{name}: output error {ratio:.2f} x its bound"
+    say(f"  max |lse err| {err_lse:.2e}, output error {ratio:.2f} x the bound, {int(empty.sum())} empty heads")
+
+
+def test_ragged_patch_attention_feeds_the_ragged_step():
+    """patch_attention_ragged -> evict_step_ragged on its normalisers == the ragged step that computes its own."""
+    w = wl("llama32_3b", E=3, Hq=6, Hkv=2, p=64, M=128, B=200)
+    n_max = w.M + w.B
+    say("patch_attention_ragged -> evict_step_ragged")
+    n = np.array([[328, 100], [5, 250], [129, 128]], dtype=np.int64)
+    budgets = np.array([128, 60, 128], dtype=np.int64)
+    q, k, v = synth.make_layer(w, layer=1, n_ctx=n_max)
+    qd, nd = q.to(DEV), torch.tensor(n, dtype=torch.int32, device=DEV)
+    bd = torch.tensor(budgets, dtype=torch.int32, device=DEV)
+    prm = ep.make_params(qd, k.to(DEV), n_cached=w.M, n_block=w.B, budget=w.M, reduce=ep.REDUCE_SUM)
+    results = []
+    for use_attn in (False, True):
+        kd, vd = k.to(DEV), v.to(DEV)
+        ws = ep.alloc_ragged_workspace(prm, ep.SELECT_PER_HEAD)
+        n_kept = torch.empty((w.E, w.Hkv), dtype=torch.int32, device=DEV)
+        scores = torch.zeros((w.E, w.Hkv, n_max), dtype=torch.float32, device=DEV)
+        keep = torch.full((w.E, w.Hkv, w.M), -1, dtype=torch.int32, device=DEV)
+        lse = None
+        if use_attn:
+            out = torch.empty_like(qd)
+            lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=DEV)
+            ep.epicache_patch_attention_ragged(prm, qd, kd, vd, nd, out, lse)
+        ep.epicache_evict_step_ragged(prm, ep.SELECT_PER_HEAD, qd, kd, vd, nd, bd, n_kept, ws, scores=scores,
+                                      keep_idx=keep, row_lse=lse)
+        torch.cuda.synchronize()
+        results.append((scores.cpu().numpy(), keep.cpu().numpy(), n_kept.cpu().numpy(), kd.cpu(), vd.cpu()))
+    (s0, keep0, nk0, k0, v0), (s1, keep1, nk1, k1, v1) = results
+    assert (nk0 == nk1).all()
+    for b in range(w.E):
+        for h in range(w.Hkv):
+            np.testing.assert_allclose(s1[b, h, :n[b, h]], s0[b, h, :n[b, h]], rtol=2e-4, atol=1e-30)
+    # the kept sets agree wherever the two score vectors order the rows identically; here: count the overlap
+    same = sum(len(set(keep0[b, h, :nk0[b, h]]) & set(keep1[b, h, :nk1[b, h]])) for b in range(w.E) for h in range(w.Hkv))
+    assert same >= 0.99 * nk0.sum()

@@ -135,3 +135,47 @@ def test_planted_mistakes_fail_the_closed_form(mistake):
                       (12 * 2 - 25 + 18 * 2 + 64 * 5) / den1])
     ok = ok and np.allclose(got[1], want1, rtol=1e-12)
     assert ok == (mistake is None)
+
+
+def test_per_head_context_lengths():
+    """Heads with their own context length (App. A.2, head-wise non-uniform retention): each head attends to its
+    own rows 0 .. n-1 and to the patch rows right behind them.  Pinned by a scalar brute force, by the weights
+    read out through identity value rows, and by NaN in every row a head must not touch."""
+    rng = np.random.default_rng(11)
+    nb, Hq, Hkv, p, d, C = 2, 4, 2, 3, 4, 12
+    q = rng.standard_normal((nb, Hq, p, d))
+    k = rng.standard_normal((nb, Hkv, C, d))
+    v = rng.standard_normal((nb, Hkv, C, d))
+    n = np.array([[5, 0], [9, 2]])
+    for causal in (True, False):
+        kk, vv = k.copy(), v.copy()
+        for b in range(nb):
+            for h in range(Hkv):
+                kk[b, h, n[b, h] + (p if causal else 0):] = np.nan
+                vv[b, h, n[b, h] + (p if causal else 0):] = np.nan
+        out, lse = orc.patch_attention(q, kk, vv, n, causal, scale=0.7)
+        for b in range(nb):
+            for hq in range(Hq):
+                h = hq // 2
+                for t in range(p):
+                    vis = list(range(n[b, h])) + ([n[b, h] + j for j in range(t + 1)] if causal else [])
+                    if not vis:
+                        assert (out[b, hq, t] == 0).all() and lse[b, hq, t] == -np.inf
+                        continue
+                    zs = [0.7 * sum(q[b, hq, t, c] * k[b, h, i, c] for c in range(d)) for i in vis]
+                    den = sum(math.exp(z) for z in zs)
+                    want = [sum(math.exp(z) / den * v[b, h, i, c] for z, i in zip(zs, vis)) for c in range(d)]
+                    np.testing.assert_allclose(out[b, hq, t], want, rtol=1e-12, atol=1e-14)
+                    assert abs(lse[b, hq, t] - math.log(den)) < 1e-12
+    # a scalar length and an array filled with it are the same thing
+    a = orc.patch_attention(q, k, v, 6, True)
+    b_ = orc.patch_attention(q, k, v, np.full((nb, Hkv), 6), True)
+    assert (a[0] == b_[0]).all() and (a[1] == b_[1]).all()
+    # identity value rows read the weights out: they sum to one over the head's own visible rows only
+    eye = np.zeros((nb, Hkv, C, C)); eye[:, :, np.arange(C), np.arange(C)] = 1.0
+    w, _ = orc.patch_attention(q, k, eye, n, True, scale=0.7)
+    for b in range(nb):
+        for hq in range(Hq):
+            for t in range(p):
+                nv = n[b, hq // 2] + t + 1
+                assert abs(w[b, hq, t, :nv].sum() - 1.0) < 1e-12 and (w[b, hq, t, nv:] == 0).all()
