@@ -54,7 +54,9 @@ __global__ __launch_bounds__(256) void compact_rows(unsigned char* __restrict__ 
 #pragma unroll
     for (int u = 0; u < kUnroll; u++) {
       const int j = c0 + u * rpr + rr;
-      src[u] = (lane_on && j < n) ? idx[j] : -1;
+      // an index outside [0, N) (not one epicache_topk writes) is clamped: the row copied is then the wrong
+      // one, but no access leaves the rows the strides were validated for
+      src[u] = (lane_on && j < n) ? min(max(idx[j], 0), pl.N - 1) : -1;
     }
   };
   load_idx(0);
