@@ -410,3 +410,29 @@ def test_pooled_sweep_feeds_its_own_counts_forward():
                                torch.from_numpy(o_v[b][h].view(np.int16)).view(torch.bfloat16))
         say(f"  step {step}: differ {differ}, oracle rows per head of item 0: {n_cached[0].tolist()}")
     assert len(set(n_cached[0].tolist())) > 1     # the heads really ended up with different lengths
+
+
+@pytest.mark.parametrize("i", range(60))
+def test_evict_step_ragged_random_shape(i):
+    """Seeded sweep of valid shapes through the ragged step: head dims of the MFMA and of the plain kernels,
+    per-head lengths from 0 to the maximum, per-item budgets from 1 to beyond the longest head, per-head and
+    pooled selection, both reductions."""
+    rng = np.random.default_rng(0xAD4 + i)
+    bf16 = bool(rng.integers(0, 2))
+    d = int(rng.choice([64, 128])) if (bf16 and rng.random() < 0.7) else int(8 * rng.integers(1, 33))
+    Hkv, G = int(rng.integers(1, 5)), int(rng.choice([1, 2, 3, 4]))
+    p = int(rng.choice([1, 7, 32, 33, 64, 90]))
+    n_max = int(rng.choice([2, 64, 65, 129, 256, 300, 513, 700]))
+    E = int(rng.integers(1, 4))
+    m_max = int(rng.choice([1, max(1, n_max // 3), max(1, n_max // 2), n_max + 3]))
+    select, pooled = SELECTS[int(rng.integers(0, 2))]
+    reduce = int(rng.integers(0, 2))
+    w = wl("tiny", E=E, Hq=Hkv * G, Hkv=Hkv, d=d, p=p, dtype="bf16" if bf16 else "f32", M=m_max, B=1,
+           recipe=str(rng.choice(["normal", "outlier_channels", "student_t"])), seed=0xE91C2000 + i)
+    say(f"evict_step_ragged random {i}: bf16={bf16} d={d} Hkv={Hkv} G={G} p={p} n_max={n_max} E={E} m_max={m_max} "
+        f"pooled={pooled} reduce={reduce}")
+    q, k, v = synth.make_layer(w, layer=i, n_ctx=n_max)
+    n_ctx = rng.integers(0, n_max + 1, size=(E, Hkv))
+    n_ctx.reshape(-1)[int(rng.integers(0, n_ctx.size))] = n_max
+    budgets = [int(x) for x in rng.integers(1, m_max + 1, size=E)]
+    check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, reduce, f"random {i}")
