@@ -88,6 +88,39 @@ def exposed_readers(ins, labels, is_producer, need):
     return found
 
 
+def _sregs(tok):
+    tok = tok.strip()
+    m = re.match(r"s\[(\d+):(\d+)\]", tok)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.match(r"s(\d+)$", tok)
+    return {int(m.group(1))} if m else set()
+
+
+def hand_written_sgpr_readers_behind_valu(ins, need):
+    """Hand-written instructions (the direct global->LDS loads and the s_mov to M0 in front of them) that read
+    an SGPR a vector instruction (v_readfirstlane and the like) wrote fewer than `need` wait states before, in
+    straight-line order: the hardware needs 5 between a VALU write of an SGPR and a memory instruction reading it."""
+    found = []
+    for i, (text, by_hand) in enumerate(ins):
+        parts = text.split(None, 1)
+        if not by_hand or len(parts) < 2 or parts[0].startswith("v_"):
+            continue
+        ops = parts[1].split(",")
+        use = set().union(*[_sregs(o) for o in (ops[1:] if parts[0].startswith("s_mov") else ops)])
+        ws = 0
+        for j in range(i - 1, -1, -1):
+            if ws >= need or not use:
+                break
+            u = ins[j][0].split(None, 1)
+            if u[0].startswith("v_") and len(u) > 1 and _sregs(u[1].split(",")[0]) & use:
+                found.append((ws, ins[j][0], text))
+                break
+            m = re.match(r"s_nop (\d+)", ins[j][0])
+            ws += int(m.group(1)) + 1 if m else 1
+    return found
+
+
 def _isa(source):
     cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
            "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "--cuda-device-only", "-S", "-o", "-",
@@ -106,6 +139,10 @@ def test_the_checker_finds_a_planted_exposure():
            ("s_endpgm", False)]
     hits = exposed_readers(ins, {".LBB0_1": 4}, lambda t: "v_mfma" in t, MFMA_8_PASS_WAIT_STATES)
     assert [h[0] for h in hits] == [1]
+    sg = [("v_readfirstlane_b32 s7, v3", False), ("s_add_i32 s8, s8, 1", False), ("s_mov_b32 m0, s7", True),
+          ("s_nop 0", True), ("global_load_lds_dwordx4 v[2:3], off", True)]
+    assert [h[0] for h in hand_written_sgpr_readers_behind_valu(sg, 5)] == [1]
+    assert hand_written_sgpr_readers_behind_valu([sg[0]] + [("s_nop 4", False)] + sg[1:], 5) == []
     padded = ins[:4] + [("s_nop 7", False), ("s_nop 3", False)] + ins[4:]
     assert exposed_readers(padded, {".LBB0_1": 4}, lambda t: "v_mfma" in t, MFMA_8_PASS_WAIT_STATES) == []
 
@@ -124,4 +161,6 @@ def test_no_hand_written_valu_reads_an_unfinished_result(source):
         after_trans = exposed_readers(ins, labels, lambda t: t.startswith(("v_exp_f32", "v_log_f32", "v_rcp_f32")),
                                       TRANS_WAIT_STATES)
         assert not after_trans, (name, after_trans[:3])
+        sgpr = hand_written_sgpr_readers_behind_valu(ins, 5)
+        assert not sgpr, (name, sgpr[:3])
     assert n_mfma_kernels >= 3
