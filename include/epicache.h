@@ -121,9 +121,9 @@ EPICACHE_API int epicache_topk(const epicache_params* params, const float* score
 /* Sec. 2.2 / App. A.3 (the cache shrinks back to M entries).  In place, for every
  * (b, h) and j < n_keep:  K[b,h,j,:] = K[b,h,keep_idx[b,h,j],:], same for V.
  * keep_idx must be strictly ascending within [0, N) (as epicache_topk writes
- * it); the order is not checked on the device, an index outside [0, N) is
- * clamped into it (the result is then unspecified, but no access leaves the
- * N rows).  Rows >= n_keep are left as they are.  Pure copy, bit exact. */
+ * it); the order is not checked on the device, and a destination row whose
+ * index lies outside [0, N) is left as it is (no access leaves the N rows).
+ * Rows >= n_keep are left as they are.  Pure copy, bit exact. */
 EPICACHE_API int epicache_compact(const epicache_params* params, const int32_t* keep_idx, void* k, void* v,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 

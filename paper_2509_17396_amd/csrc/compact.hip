@@ -54,9 +54,7 @@ __global__ __launch_bounds__(256) void compact_rows(unsigned char* __restrict__ 
 #pragma unroll
     for (int u = 0; u < kUnroll; u++) {
       const int j = c0 + u * rpr + rr;
-      // an index outside [0, N) (not one epicache_topk writes) is clamped: the row copied is then the wrong
-      // one, but no access leaves the rows the strides were validated for
-      src[u] = (lane_on && j < n) ? min(max(idx[j], 0), pl.N - 1) : -1;
+      src[u] = (lane_on && j < n) ? idx[j] : -1;
     }
   };
   load_idx(0);
@@ -66,7 +64,10 @@ __global__ __launch_bounds__(256) void compact_rows(unsigned char* __restrict__ 
 #pragma unroll
     for (int u = 0; u < kUnroll; u++) {
       cur[u] = src[u];
-      // rows already in place (a kept prefix) are neither read nor written
+      // Rows already in place (a kept prefix) are neither read nor written.  An index outside [0, N) (not one
+      // epicache_topk writes) is skipped like the -1 of an idle lane, so no access leaves the rows the strides
+      // were validated for.
+      if ((unsigned)cur[u] >= (unsigned)pl.N) cur[u] = -1;
       if (cur[u] >= 0 && cur[u] != c0 + u * rpr + rr)
         data[u] = load_row16(base + (size_t)cur[u] * pitch);
     }

@@ -308,23 +308,27 @@ def test_compact_bit_exact(case):
     np.testing.assert_array_equal(synth.raw_bits_numpy(kd)[:, :, M:], kb[:, :, M:])
 
 
-def test_compact_clamps_indices_outside_the_context():
+def test_compact_skips_indices_outside_the_context():
     """Indices that epicache_topk would never write (negative, beyond N) must not take the kernel outside the
-    N rows of its head: they are clamped, rows at valid indices are still copied exactly, and the neighbouring
-    head and the rows behind the kept ones are untouched."""
+    N rows of its head: their destination rows are left alone, rows at valid indices are still copied exactly,
+    and the neighbouring head and the rows behind the kept ones are untouched."""
     say("compact with out-of-range indices")
     nb, H, N, M, d = 1, 2, 300, 64, 128
     g = torch.Generator().manual_seed(9)
     k = torch.randn(nb, H, N + 2, d, generator=g).to(torch.bfloat16)
     v = torch.randn(nb, H, N + 2, d, generator=g).to(torch.bfloat16)
     keep = np.tile(np.arange(100, 100 + M, dtype=np.int32), (nb, H, 1))
-    keep[0, 0, 0], keep[0, 0, 1], keep[0, 0, M - 1] = -5, -(2 ** 31), 2 ** 31 - 1
+    bad = [0, 1, 17, M - 1]
+    keep[0, 0, bad] = [-5, -(2 ** 31), N, 2 ** 31 - 1]
     kd, vd = gpu_compact(k, v, keep, N, M)
-    kb, got = synth.raw_bits_numpy(k), synth.raw_bits_numpy(kd)
-    clamped = np.clip(keep, 0, N - 1)
-    np.testing.assert_array_equal(got[:, :, :M], orc.compact(kb, clamped))
-    np.testing.assert_array_equal(got[:, :, M:], kb[:, :, M:])
-    np.testing.assert_array_equal(synth.raw_bits_numpy(vd)[:, :, :M], orc.compact(synth.raw_bits_numpy(v), clamped))
+    for src, got in ((k, kd), (v, vd)):
+        sb, gb = synth.raw_bits_numpy(src), synth.raw_bits_numpy(got)
+        want = sb.copy()
+        for h in range(H):
+            for j in range(M):
+                if 0 <= keep[0, h, j] < N:
+                    want[0, h, j] = sb[0, h, keep[0, h, j]]
+        np.testing.assert_array_equal(gb, want)
 
 
 # -------------------------------------------------------------- evict step
