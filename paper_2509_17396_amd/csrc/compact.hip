@@ -17,8 +17,8 @@ namespace {
 constexpr int kUnroll = 8;  // row rounds in flight per thread: 8 x 16 B
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-// Every byte is touched exactly once, so loads and stores bypass the caches' retention
-// (non-temporal): measured 5.5 TB/s against 3.7 TB/s with default caching on this pattern.
+// Every byte is touched exactly once, so loads and stores are marked non-temporal: among the cache-policy
+// combinations tried (nt, sc0, sc1 on loads and stores) nt on both is the fastest, 4 % ahead of the default.
 __device__ __forceinline__ u32x4 load_row16(const unsigned char* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
