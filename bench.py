@@ -296,6 +296,10 @@ def main():
                                 "gbs": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9,
                                 "frac_hbm_peak": (bytes_topk + bytes_compact) / (t_topk + t_compact) / 1e9 / PEAK_HBM_GBS},
     }
+    score_traffic = measured_traffic(w.name, "score")
+    if score_traffic:   # HBM bytes the two passes move per launch (rocprofv3 counters, profiles/), over the live time
+        stages["score"]["hbm_gbs_measured_traffic"] = score_traffic / t_score / 1e9
+        stages["score"]["frac_hbm_peak_measured_traffic"] = score_traffic / t_score / 1e9 / PEAK_HBM_GBS
     if t_score >= t_compact + t_topk:
         a = flops_score / t_score / 1e12
         roofline = {"kernel": "score (score_stats + score_reduce)", "bound": "mfma", "achieved": a,
