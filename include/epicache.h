@@ -75,7 +75,7 @@ typedef struct epicache_params {
   int32_t patch_len;      /* p >= 1 scoring queries per query head (Sec. 2.3)                 */
   int32_t dtype;          /* epicache_dtype of Q, K, V                                        */
   int32_t reduce;         /* epicache_reduce over the G*p rows that vote for one KV head      */
-  float softmax_scale;    /* logit scale; 0 selects 1/sqrt(head_dim)                          */
+  float softmax_scale;    /* logit scale; 0 selects 1/sqrt(head_dim); at most 1e6             */
   int32_t causal_patch;   /* 0: softmax over the N context keys only.  1: rows [N, N+patch_len) of */
                           /* K[b,h] hold the patch's own keys and patch token t also attends to    */
                           /* patch keys 0..t, as in the model's forward pass (Sec. 2.3); only the  */

@@ -43,6 +43,7 @@ int make_plan(const epicache_params* prm, Plan* out) {
   if (prm->reduce != EPICACHE_REDUCE_MAX && prm->reduce != EPICACHE_REDUCE_SUM)
     return EPICACHE_ERR_INVALID_ARG;
   if (!(prm->softmax_scale >= 0.0f) || isinf(prm->softmax_scale)) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->softmax_scale > 1.0e6f) return EPICACHE_ERR_UNSUPPORTED;  // the kernels' sentinels times the scale stay finite
   if ((prm->causal_patch != 0 && prm->causal_patch != 1) || prm->reserved != 0) return EPICACHE_ERR_INVALID_ARG;
   const int64_t N64 = (int64_t)prm->n_cached + prm->n_block;
   if (N64 < 1) return EPICACHE_ERR_INVALID_ARG;

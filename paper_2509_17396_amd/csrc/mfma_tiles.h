@@ -123,8 +123,10 @@ __device__ __forceinline__ void read_frags(bf16x8 (&f)[HD / 16], const unsigned 
 
 // Finite sentinels instead of infinities keep the running-max updates branch-free and NaN-free:
 // kNoMax is the "no key seen yet" maximum, kMasked (< kNoMax) the logit of a key that must not count.
-constexpr float kNoMax = -1.5e38f;
-constexpr float kMasked = -3.0e38f;
+// Their products with c2 = scale * log2(e) must stay finite (no inf - inf in the exponent arithmetic), which
+// holds for every scale the host accepts (<= 1e6); raw dot products are assumed to lie above kNoMax.
+constexpr float kNoMax = -1.0e30f;
+constexpr float kMasked = -2.0e30f;
 
 template <int KS>
 __device__ __forceinline__ void mfma_chain(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS]) {

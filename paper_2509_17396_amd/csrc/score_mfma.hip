@@ -44,7 +44,7 @@ namespace {
 // seen no key yet has m = kNoMax; masked keys and the filler tile that precedes the
 // first real one hold kMasked < kNoMax, so folding them in leaves (m, D) untouched
 // (their exp2 underflows to exactly 0 and the max does not move).  Raw dot products
-// are assumed to lie above kNoMax.
+// are assumed to lie above kNoMax (-1e30).
 struct RowStat {
   float m, D;  // running max of the raw dot products; running sum of exp2((dot - m) * c2)
 };
@@ -58,18 +58,16 @@ __device__ __forceinline__ void stats_begin(const f32x16& P, const RowStat& st, 
   corr = ex2((st.m - mn) * c2);  // exactly 1 when the max did not move
 }
 
-// Which accumulator values enter the arithmetic pipeline in each MFMA slot of a unit.  An MFMA
-// leaves the issue port free for about half of its 32 clocks, so the softmax arithmetic is spread
-// evenly over the KS slots; and because dependent VALU / transcendental ops have several clocks of
-// latency, it is staggered: the values that get their multiply-add in slot j get their exp2 in
-// slot j+1 and are summed in slot j+2, so the instructions inside one slot never wait on each other.
+// Which accumulator values enter the arithmetic pipeline in each MFMA slot of a unit.  Independent vector
+// instructions issue in the shadow of an MFMA, so the softmax arithmetic is spread evenly over the KS slots;
+// and because dependent VALU / transcendental ops have several clocks of latency, it is staggered: the
+// values that get their multiply-add in slot j get their exp2 in slot j+1 and are summed in slot j+2, so
+// the instructions inside one slot never wait on each other.
 template <int KS> struct Slots;
 template <> struct Slots<8> {
-  static constexpr int stats[9] = {0, 0, 3, 6, 8, 10, 12, 14, 16};  // slot 0 finds the new maximum
   static constexpr int reduce[9] = {0, 2, 4, 6, 8, 10, 12, 14, 16};
 };
 template <> struct Slots<4> {
-  static constexpr int stats[5] = {0, 0, 6, 11, 16};
   static constexpr int reduce[5] = {0, 4, 8, 12, 16};
 };
 
@@ -116,30 +114,37 @@ __device__ __forceinline__ float stats_group(const f32x16& P, int g, float c2, f
 
 // acc <- MFMA chain over head_dim (A rows = a-frag rows, B columns = b-frag rows), interleaved
 // with folding P, the tile finished one unit earlier, into its row statistics.
+// The reference st.m of a row only has to keep the exponentials in range, so the fast path does not look
+// for the tile's maximum at all (12 of ~62 instructions per unit): it sums exp2((dot - st.m) * c2) as is and
+// checks the sum.  A sum beyond kRebase (a dot product more than ~60 / c2 above the reference, or a row
+// that has no reference yet: st.m = kNoMax sends every real dot product to +inf) takes the exact path
+// below, which moves the reference to the true maximum.  Wave-uniform branch, taken for the first tile of
+// a row and then only when the logits climb by a factor of 2^60 in weight.
+constexpr float kRebase = 1.0e18f;
+
 template <int KS, int J>
 __device__ __forceinline__ void stats_slot(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                            const f32x16& P, float c2, float nmc, float (&x)[16], float& s0,
                                            float& s1) {
   using SL = Slots<KS>;
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], acc, 0, 0, 0);
+  const f32x16 zero = {0};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[J], b[J], J == 0 ? zero : acc, 0, 0, 0);
   fence_sched();
-  stats_stage_fma<SL::stats[J], SL::stats[J + 1]>(x, P, c2, nmc);
-  stage_exp<SL::stats[J - 1], SL::stats[J]>(x);
-  if constexpr (J >= 2) stage_add<SL::stats[J - 2], SL::stats[J - 1]>(x, s0, s1);
+  stats_stage_fma<SL::reduce[J], SL::reduce[J + 1]>(x, P, c2, nmc);
+  if constexpr (J >= 1) stage_exp<SL::reduce[J - 1], SL::reduce[J]>(x);
+  if constexpr (J >= 2) stage_add<SL::reduce[J - 2], SL::reduce[J - 1]>(x, s0, s1);
   fence_sched();
 }
+
+__device__ __forceinline__ void stats_fold(const f32x16& P, RowStat& st, float c2);
 
 template <int KS>
 __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
                                            const f32x16& P, RowStat& st, float c2) {
   using SL = Slots<KS>;
-  float mn, nmc, corr, s0 = 0.f, s1 = 0.f, x[16];
-  const f32x16 zero = {0};
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], zero, 0, 0, 0);
-  fence_sched();
-  stats_begin(P, st, c2, mn, nmc, corr);
-  pin(nmc), pin(corr);
-  fence_sched();
+  float s0 = 0.f, s1 = 0.f, x[16];
+  const float nmc = -st.m * c2;
+  stats_slot<KS, 0>(acc, a, b, P, c2, nmc, x, s0, s1);
   stats_slot<KS, 1>(acc, a, b, P, c2, nmc, x, s0, s1);
   stats_slot<KS, 2>(acc, a, b, P, c2, nmc, x, s0, s1);
   stats_slot<KS, 3>(acc, a, b, P, c2, nmc, x, s0, s1);
@@ -150,11 +155,12 @@ __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], c
     stats_slot<KS, 7>(acc, a, b, P, c2, nmc, x, s0, s1);
   }
   // drain the pipeline: last exp2 stage, last two sum stages
-  stage_exp<SL::stats[KS - 1], SL::stats[KS]>(x);
-  stage_add<SL::stats[KS - 2], SL::stats[KS - 1]>(x, s0, s1);
-  stage_add<SL::stats[KS - 1], SL::stats[KS]>(x, s0, s1);
-  st.D = fmaf(st.D, corr, s0 + s1);
-  st.m = mn;
+  stage_exp<SL::reduce[KS - 1], SL::reduce[KS]>(x);
+  stage_add<SL::reduce[KS - 2], SL::reduce[KS - 1]>(x, s0, s1);
+  stage_add<SL::reduce[KS - 1], SL::reduce[KS]>(x, s0, s1);
+  const float D = st.D + (s0 + s1);
+  if (__any(!(D <= kRebase))) stats_fold(P, st, c2);  // some row needs a new reference: exact path for the wave
+  else st.D = D;
   fence_sched();
 }
 

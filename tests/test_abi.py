@@ -82,6 +82,7 @@ def test_workspace_size_is_host_only_and_monotone():
     ("reduce", 2, ep.ERR_INVALID_ARG),
     ("softmax_scale", -1.0, ep.ERR_INVALID_ARG),
     ("softmax_scale", float("nan"), ep.ERR_INVALID_ARG),
+    ("softmax_scale", 2.0e6, ep.ERR_UNSUPPORTED),
     ("causal_patch", 2, ep.ERR_INVALID_ARG),
     ("causal_patch", 1, ep.ERR_INVALID_ARG),      # capacity 640 = N: no room for the 16 patch keys
     ("reserved", 1, ep.ERR_INVALID_ARG),

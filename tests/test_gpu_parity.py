@@ -154,6 +154,41 @@ def test_score_explicit_scale_and_strided_views():
         pu.assert_scores_close(got, want, pu.RTOL_BF16, "strided")
 
 
+@pytest.mark.parametrize("scale", [3.0, 40.0, 1e-4], ids=["scale3", "scale40", "scale1e-4"])
+@pytest.mark.parametrize("causal", [0, 1], ids=["context_only", "causal_patch"])
+def test_score_and_patch_attention_with_extreme_scales(scale, causal):
+    """Logit scales far from 1/sqrt(d): near one-hot rows (the sentinels of the kernels times the scale must
+    stay finite, the lazy softmax reference has to rebase) and near-uniform rows, on the MFMA and the plain path."""
+    for name, over in (("llama32_3b", dict(E=1, Hq=6, Hkv=2, p=40)), ("tiny", dict(E=1, Hq=4, Hkv=2, p=9, d=24))):
+        w = wl(name, **over)
+        N = 700
+        say(f"extreme scale {scale} causal={causal} {name}")
+        q, k, v = synth.make_layer(w, layer=5, n_ctx=N + w.p)
+        qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+        qq, kk = pu.oracle_inputs(q, k)
+        # the fp32 tolerance is derived for logits of order 10; the rounding of a logit held in fp32 grows with
+        # its magnitude, i.e. with the scale
+        rtol = max(pu.rtol_for(q.dtype), 1e-5 * 10 * scale)
+        for reduce in (orc.REDUCE_MAX, orc.REDUCE_SUM):
+            prm = ep.make_params(qd, kd, n_cached=0, n_block=N, budget=5, reduce=reduce, softmax_scale=scale,
+                                 causal_patch=causal)
+            ws = ep.alloc_workspace(prm)
+            scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+            ep.epicache_score(prm, qd, kd, scores, ws)
+            torch.cuda.synchronize()
+            want = (orc.score_causal_patch(qq, kk, N, reduce, scale=scale) if causal
+                    else orc.score(qq, kk[:, :, :N], N, reduce, scale=scale))
+            pu.assert_scores_close(scores.cpu().numpy(), want, rtol, f"{name} scale={scale} reduce={reduce}")
+        out = torch.empty_like(qd)
+        lse = torch.empty(qd.shape[:3], dtype=torch.float32, device=DEV)
+        ep.epicache_patch_attention(prm, qd, kd, vd, out, lse)
+        torch.cuda.synchronize()
+        _, o_lse = orc.patch_attention(qq, kk, synth.to_f64_numpy(v), N, bool(causal), scale=scale)
+        got = lse.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        assert np.abs(got - o_lse).max() <= 2e-5 * (1 + np.abs(o_lse).max())
+
+
 def test_score_mfma_agrees_with_generic_kernel_closely():
     """Same bf16 inputs through the MFMA path (d=128) and, zero-padded to d=136, through the
     generic fp32-FMA path: both must sit within the tolerance of the oracle, and of each other."""
