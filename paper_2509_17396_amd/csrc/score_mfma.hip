@@ -645,42 +645,19 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   wait_vmem();
   __syncthreads();  // first key tile and nlse[] are in LDS
 
-  int buf = 0;
-  for (int t = t_begin; t < t_end; t++) {
-    const unsigned char* cur = lds + buf * TL::kTileBytes;
-    if (t + 1 < t_end) stage_keys(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
-    float cs[2] = {kNeutral, kNeutral};  // this wave's rows, keys ks*32 + l32 of the tile
-    if (active) {
-      // units (ks, s): key half ks, query sub-tile s; unit u accumulates into accA/accB (u even/odd)
-      // while unit u-1 is reduced over its 16 rows into cs[ks of u-1]
-      bf16x8 kf[KS];
-      f32x16 accA, accB;
-      read_frags<HD>(kf, cur, 0, l32, hi);
-#pragma unroll
-      for (int u = 0; u < 2 * NQ; u++) {
-        const int s = u % NQ, sp = (u + 2 * NQ - 1) % NQ, ksp = (u - 1) / NQ;
-        if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
-        float nl[16];  // minus lse of the 16 rows this lane holds of the previous unit
-        if (u > 0) read_nlse(nl, nlse, row0 + sp * 32, hi);
-        if (u == 0) mfma_chain<KS>(accA, qf[0], kf);
-        else if (u & 1) reduce_unit<KS, REDUCE>(accB, qf[s], kf, accA, nl, cs[ksp], c2);
-        else            reduce_unit<KS, REDUCE>(accA, qf[s], kf, accB, nl, cs[ksp], c2);
-      }
-      {
-        float nl[16];
-        read_nlse(nl, nlse, row0 + (NQ - 1) * 32, hi);
-        col_fold<KS, REDUCE>(accB, nl, cs[1], c2);  // last unit: odd index, key half 1
-      }
-    }
+  // The pipeline runs across tile boundaries: the last unit of tile t-1 (in accB) is reduced while the first
+  // chain of tile t is issued, so the column partials of a tile are complete one unit into the next tile and
+  // its scores are written one barrier later than its keys were consumed.
+  auto exchange = [&](const float (&c)[2], int t) {  // this wave's partials of tile t -> part[t & 1]
 #pragma unroll
     for (int ks = 0; ks < 2; ks++) {
       // lanes l and l^32 hold the same key over disjoint query rows
-      const float o = __shfl_xor(cs[ks], 32);
-      const float v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(cs[ks], o) : cs[ks] + o;
+      const float o = __shfl_xor(c[ks], 32);
+      const float v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(c[ks], o) : c[ks] + o;
       if (hi == 0) part[t & 1][wave][ks * 32 + l32] = v;
     }
-    wait_vmem();
-    __syncthreads();  // tile t+1 staged, part[t & 1] complete; it is rewritten two barriers from now
+  };
+  auto write_scores = [&](int t) {  // after the barrier that completes part[t & 1]
     if (tid < 64) {
       const int key = t * kKeyTile + tid;
       if (key < N) {
@@ -691,8 +668,53 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
         scores[(size_t)bh * pl.N + key] = REDUCE == EPICACHE_REDUCE_MAX ? ex2(v) : v;
       }
     }
+  };
+
+  int buf = 0;
+  f32x16 accA, accB;                             // accB after a tile: its last unit, still to be reduced
+#pragma unroll
+  for (int v = 0; v < 16; v++) accB[v] = kMasked;  // before the first tile: a filler whose weights are 0; what it
+                                                   // leaves in cs_prev is never exchanged
+  float cs_prev[2] = {kNeutral, kNeutral};       // partials of the previous tile (keys ks*32 + l32)
+  for (int t = t_begin; t < t_end; t++) {
+    const unsigned char* cur = lds + buf * TL::kTileBytes;
+    if (t + 1 < t_end) stage_keys(lds0 + (buf ^ 1) * TL::kTileBytes, t + 1);
+    float cs[2] = {kNeutral, kNeutral};  // this wave's rows, keys ks*32 + l32 of the tile
+    if (active) {
+      // units (ks, s): key half ks, query sub-tile s; unit u accumulates into accA/accB (u even/odd)
+      // while unit u-1 is reduced over its 16 rows into cs[ks of u-1]
+      bf16x8 kf[KS];
+      read_frags<HD>(kf, cur, 0, l32, hi);
+#pragma unroll
+      for (int u = 0; u < 2 * NQ; u++) {
+        const int s = u % NQ, sp = (u + 2 * NQ - 1) % NQ, ksp = (u - 1) / NQ;
+        if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
+        float nl[16];  // minus lse of the 16 rows this lane holds of the previous unit
+        read_nlse(nl, nlse, row0 + sp * 32, hi);
+        if (u == 0) {
+          reduce_unit<KS, REDUCE>(accA, qf[0], kf, accB, nl, cs_prev[1], c2);  // last unit of tile t-1
+        } else if (u & 1) {
+          reduce_unit<KS, REDUCE>(accB, qf[s], kf, accA, nl, cs[ksp], c2);
+        } else {
+          reduce_unit<KS, REDUCE>(accA, qf[s], kf, accB, nl, cs[ksp], c2);
+        }
+      }
+    }
+    if (t > t_begin) exchange(cs_prev, t - 1);
+    wait_vmem();
+    __syncthreads();  // tile t+1 staged, part[(t-1) & 1] complete; it is rewritten two barriers from now
+    if (t > t_begin) write_scores(t - 1);
+    cs_prev[0] = cs[0], cs_prev[1] = cs[1];
     buf ^= 1;
   }
+  if (active) {
+    float nl[16];
+    read_nlse(nl, nlse, row0 + (NQ - 1) * 32, hi);
+    col_fold<KS, REDUCE>(accB, nl, cs_prev[1], c2);  // last unit of the last tile: odd index, key half 1
+  }
+  exchange(cs_prev, t_end - 1);
+  __syncthreads();
+  write_scores(t_end - 1);
 }
 
 template <int HD, int NQ, int NW>
