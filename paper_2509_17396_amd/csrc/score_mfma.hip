@@ -651,9 +651,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   auto exchange = [&](const float (&c)[2], int t) {  // this wave's partials of tile t -> part[t & 1]
 #pragma unroll
     for (int ks = 0; ks < 2; ks++) {
-      // lanes l and l^32 hold the same key over disjoint query rows
-      const float o = __shfl_xor(c[ks], 32);
-      const float v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(c[ks], o) : c[ks] + o;
+      // lanes l and l^32 hold the same key over disjoint query rows; the swap leaves the lower half's values
+      // in both halves of one register and the upper half's in both halves of the other (vector ALU, no LDS)
+      const unsigned int bits = __float_as_uint(c[ks]);
+      const auto r = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+      const float lo = __uint_as_float(r[0]), up = __uint_as_float(r[1]);
+      const float v = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(lo, up) : lo + up;
       if (hi == 0) part[t & 1][wave][ks * 32 + l32] = v;
     }
   };
