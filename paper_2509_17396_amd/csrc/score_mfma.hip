@@ -3,8 +3,9 @@
 // Eq. 1 needs every row's softmax normaliser over all N context keys before a
 // single column value is final, and the R x N logits of one KV head do not fit
 // on chip, so Q.K^T is evaluated twice:
-//   pass 1 (score_stats):  per query row, running (max, sum of exp2) over the
-//                          keys of one key split  -> stats[bh][split][row]
+//   pass 1 (score_stats):  per query row, a reference logit (the maximum, or a value
+//                          within 2^60 in weight of it) and the sum of exp2 relative
+//                          to it over the keys of one key split -> stats[bh][split][row]
 //   pass 2 (score_reduce): per context key, reduce exp2(logit - lse_row) over
 //                          all R = G*p rows (max or sum) -> scores[bh][key]
 // Both use v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  The operand order
@@ -46,7 +47,7 @@ namespace {
 // (their exp2 underflows to exactly 0 and the max does not move).  Raw dot products
 // are assumed to lie above kNoMax (-1e30).
 struct RowStat {
-  float m, D;  // running max of the raw dot products; running sum of exp2((dot - m) * c2)
+  float m, D;  // reference (a raw dot product at or below the running maximum); running sum of exp2((dot - m) * c2)
 };
 
 __device__ __forceinline__ void stats_begin(const f32x16& P, const RowStat& st, float c2, float& mn,
