@@ -14,8 +14,9 @@
  *     epicache_layer_budgets are HOST pointers.  Every other pointer is a
  *     DEVICE pointer, 16-byte aligned, owned by the caller.  The library never
  *     allocates, frees or retains device memory and keeps no state between
- *     calls, so it may be called from several host threads and its calls may
- *     be captured into a HIP graph.
+ *     calls (epicache_evict_step_static documents the one exception), so it may
+ *     be called from several host threads and its calls may be captured into a
+ *     HIP graph.
  *   - A call validates its arguments on the host, enqueues its kernels on
  *     `hip_stream` (a hipStream_t; NULL = the default stream) and returns
  *     without synchronising.  The return value is an epicache_status; it
@@ -135,6 +136,22 @@ EPICACHE_API int epicache_compact(const epicache_params* params, const int32_t* 
 EPICACHE_API int epicache_evict_step(const epicache_params* params, const void* q, void* k, void* v,
                         float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc) and have no workspace at hand: epicache_evict_step with the workspace
+ * taken from an array of EPICACHE_STATIC_SCRATCH_BYTES that the library's code object holds in the memory of
+ * every GPU it is loaded on, from load until the process ends.  Arguments, results and status codes as
+ * epicache_evict_step; the call allocates and frees nothing.  A request whose workspace (what
+ * epicache_workspace_size reports, less the parts covered by scores_opt / keep_idx_opt when given) exceeds
+ * the array returns EPICACHE_ERR_WORKSPACE_TOO_SMALL and enqueues nothing.  The first call on a device looks
+ * up the array's address on that device (the device current at the call must be the one hip_stream belongs
+ * to) and keeps it; that table is the only state the library holds.  All calls on one GPU share the one
+ * array, which keeps whatever the last call left in it (nothing in it needs to start at zero: every part is
+ * written before it is read within a call), so calls that overlap on one GPU, on different streams or from
+ * different threads, race: order them on one stream or with events. */
+#define EPICACHE_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const void* q, void* k, void* v,
+                        float* scores_opt, int32_t* keep_idx_opt, void* hip_stream);
 
 /* epicache_evict_step with the scoring done by epicache_score_lse: for callers whose prefill
  * attention kernel already returned each patch row's log-sum-exp (row_lse as documented there).

@@ -23,7 +23,7 @@ SELECT_PER_HEAD, SELECT_POOLED = 0, 1
 
 ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
-    "epicache_evict_step", "epicache_evict_step_lse", "epicache_layer_budgets",
+    "epicache_evict_step", "epicache_evict_step_static", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
     "epicache_evict_step_ragged", "epicache_score_keydiff", "epicache_patch_attention",
     "epicache_patch_attention_ragged",
@@ -90,6 +90,7 @@ def load() -> ctypes.CDLL:
     lib.epicache_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.epicache_compact.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.epicache_evict_step_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_layer_budgets.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
@@ -184,6 +185,14 @@ def epicache_evict_step(params: Params, q, k, v, workspace, scores=None, keep_id
     _check(load().epicache_evict_step(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
                                       _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def epicache_evict_step_static(params: Params, q, k, v, scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step_static(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
+                                             _ptr(keep_idx), _stream()), "epicache_evict_step_static")
 
 
 def epicache_evict_step_lse(params: Params, q, k, v, row_lse, workspace, scores=None, keep_idx=None) -> None:

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "epicache_internal.h"
@@ -177,6 +178,32 @@ static int run_score_lse(const Plan& pl, const void* q, const void* k, const flo
   hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, true, stream)
                              : launch_score_generic(p1, q, k, scores, stats, true, stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
+}
+
+// Workspace of epicache_evict_step_static: one array per GPU, held from the moment the code object is
+// loaded until the process ends.  Host code never uses the array's name as an address: its device address
+// is looked up once per device (static_scratch) and that pointer is what the kernels receive.
+constexpr size_t kStaticScratchBytes = EPICACHE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, null until looked up
+
+// Device address of the current device's copy of `scratch`; null if the lookup fails.
+static void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    scratch_ptr[dev] = ptr;
+  }
+  return scratch_ptr[dev];
 }
 
 }  // namespace epicache
@@ -373,6 +400,21 @@ int epicache_evict_step(const epicache_params* params, const void* q, void* k, v
                         size_t workspace_bytes, void* hip_stream) {
   return evict_step_impl(params, q, k, v, nullptr, false, scores_opt, keep_idx_opt, workspace,
                          workspace_bytes, hip_stream);
+}
+
+int epicache_evict_step_static(const epicache_params* params, const void* q, void* k, void* v,
+                               float* scores_opt, int32_t* keep_idx_opt, void* hip_stream) {
+  Plan pl;
+  int st = make_plan(params, &pl);
+  if (st != EPICACHE_OK) return st;
+  // only the parts of the workspace that the caller does not supply have to fit the array
+  const size_t need = !scores_opt ? (!keep_idx_opt ? pl.ws_total : pl.off_keep) :
+                      (!keep_idx_opt ? pl.ws_total : pl.off_scores);
+  if (need > kStaticScratchBytes) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  void* ws = static_scratch();
+  if (!ws) return EPICACHE_ERR_DEVICE;
+  return evict_step_impl(params, q, k, v, nullptr, false, scores_opt, keep_idx_opt, ws,
+                         kStaticScratchBytes, hip_stream);
 }
 
 int epicache_evict_step_lse(const epicache_params* params, const void* q, void* k, void* v,

@@ -110,6 +110,17 @@ def test_bad_params_are_rejected_before_any_launch(field, value, status):
                                    dummy, 1 << 30, None) == status
 
 
+def test_static_scratch_entry_point_refuses_oversized_requests_on_the_host():
+    q = torch.empty(64, 32, 256, 128, dtype=torch.bfloat16, device="meta")
+    k = torch.empty(64, 8, 24576, 128, dtype=torch.bfloat16, device="meta")
+    prm = ep.make_params(q, k, n_cached=16384, n_block=8192, budget=16384, reduce=ep.REDUCE_SUM)
+    assert ep.epicache_workspace_size(prm) > ep.STATIC_SCRATCH_BYTES
+    a, b = ctypes.c_void_p(4096), ctypes.c_void_p(8192)
+    lib = ep.load()
+    assert lib.epicache_evict_step_static(ctypes.byref(prm), a, a, b, None, None, None) == ep.ERR_WORKSPACE_TOO_SMALL
+    assert lib.epicache_evict_step_static(ctypes.byref(_params(budget=0)), a, a, b, None, None, None) == ep.ERR_INVALID_ARG
+
+
 def test_null_misaligned_and_small_workspace_are_rejected():
     prm = _params()
     lib = ep.load()
