@@ -77,6 +77,28 @@ def oracle_score_one_head(q: torch.Tensor, k: torch.Tensor, b: int, h: int, N: i
     return orc.score(qq, kk, N, reduce, scale)[0, 0]
 
 
+def oracle_score_heads(q: torch.Tensor, k: torch.Tensor, heads, N: int, reduce: int, scale=None, workers=None):
+    """Oracle scores of several (batch item, KV head) pairs of a large tensor, one oracle call per head,
+    the calls spread over host threads (numpy releases the interpreter lock inside its loops).
+    Returns {(b, h): [N] float64}."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    G = q.shape[1] // k.shape[1]
+    heads = list(heads)
+    host = {}
+    for (b, h) in heads:  # exact widening of the device bits, done once, serially
+        host[(b, h)] = (synth.to_f64_numpy(q[b:b + 1, h * G:(h + 1) * G]), synth.to_f64_numpy(k[b:b + 1, h:h + 1, :N]))
+    if workers is None:
+        workers = max(1, min(16, os.cpu_count() or 1))
+
+    def one(bh):
+        qq, kk = host[bh]
+        return bh, orc.score(qq, kk, N, reduce, scale)[0, 0]
+
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        return dict(pool.map(one, heads))
+
+
 def assert_ragged_keep_matches(gpu_keep, oracle_rows, budgets, pooled: bool, rtol: float, what=""):
     """Ragged counterpart of assert_keep_matches.  gpu_keep[b][h]: kept indices of head (b, h);
     oracle_rows[b][h]: float64 oracle scores of its n_ctx rows.  Counts are exact (per head, or per

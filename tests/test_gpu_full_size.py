@@ -4,7 +4,9 @@ Inputs are generated on the GPU by the seeded generator; the oracle gets the ver
 same bits (copied back) for a sample of (batch item, KV head) pairs, which it can
 compute one by one, and the rest is checked through properties that hold at any
 size.  The first test is the exact launch configuration that bench.py times."""
+import os
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -75,41 +77,89 @@ def test_config2_all_layers_folded_as_benchmarked(reduce):
     k, v = k0.clone(), v0.clone()
     scores, keep = evict_on_gpu(q, k, v, w.M, w.N, reduce)
     nb = w.L * w.E
-    samples = [(0, 0), (5, 3), (57, 7), (nb - 1, w.Hkv - 1)]
+    samples = [(0, 0), (5, 3), (57, 7), (nb - 1, w.Hkv - 1), (1, 1), (30, 2), (77, 4), (110, 6)]
     differ = check_sampled(q, k0, v0, k, v, scores, keep, w.M, w.N, reduce, samples, "config2")
     say(f"  kept-set differences inside the band: {differ}")
 
 
-FULL_LAYER_CASES = [
-    ("llama31_8b", [(0, 0), (3, 7)]),
-    ("qwen25_7b", [(0, 0), (7, 3)]),
-    ("stress", [(0, 0), (15, 7)]),
-]
+def check_heads_against_oracle(q, k0, scores, keep, M, N, reduce, heads, what):
+    """Scores and kept sets of the given (b, h) pairs against the oracle.  Returns (kept-set differences
+    inside the tolerance band, worst relative score error)."""
+    rtol = pu.rtol_for(q.dtype)
+    ref = pu.oracle_score_heads(q, k0, heads, N, reduce)
+    differ, worst = 0, 0.0
+    for (b, h) in heads:
+        o = ref[(b, h)]
+        worst = max(worst, pu.assert_scores_close(scores[b, h].cpu().numpy(), o, rtol, f"{what} b={b} h={h}"))
+        differ += pu.assert_keep_matches(keep[b:b + 1, h:h + 1].cpu().numpy(), o[None, None], M, rtol, f"{what} b={b} h={h}")
+    return differ, worst
+
+
+WHOLE_LAYER_CASES = ["llama31_8b", "qwen25_7b", "stress"]
 
 
 @pytest.mark.parametrize("reduce", [orc.REDUCE_SUM, orc.REDUCE_MAX], ids=["sum", "max"])
-@pytest.mark.parametrize("name,samples", FULL_LAYER_CASES, ids=[c[0] for c in FULL_LAYER_CASES])
-def test_configs_3_to_5_one_layer_full_shape(name, samples, reduce):
+@pytest.mark.parametrize("name", WHOLE_LAYER_CASES)
+def test_configs_3_to_5_whole_layer_every_head(name, reduce):
+    """One layer of each of the three large workloads at its full shape: every (episode, KV head) of the
+    layer is compared with the oracle (scores elementwise, kept sets by the band rule), and the compaction
+    of the whole layer is checked bit for bit on the device."""
     w = synth.WORKLOADS[name]
-    say(f"{name} one layer E={w.E} N={w.N} R={w.R} reduce={reduce}")
+    say(f"{name} whole layer E={w.E} Hkv={w.Hkv} N={w.N} R={w.R} reduce={reduce}")
     q, k0, v0 = synth.make_layer(w, layer=1, device=DEV)
     k, v = k0.clone(), v0.clone()
     scores, keep = evict_on_gpu(q, k, v, w.M, w.N, reduce)
-    differ = check_sampled(q, k0, v0, k, v, scores, keep, w.M, w.N, reduce, samples, name)
-    say(f"  kept-set differences inside the band: {differ}")
+    check_sampled(q, k0, v0, k, v, scores, keep, w.M, w.N, reduce, [], name)
+    heads = [(b, h) for b in range(w.E) for h in range(w.Hkv)]
+    differ, worst = check_heads_against_oracle(q, k0, scores, keep, w.M, w.N, reduce, heads, name)
+    say(f"  {len(heads)} heads against the oracle: worst relative score error {worst:.2e}, "
+        f"kept-set differences inside the band {differ} of {len(heads) * w.M} kept tokens")
 
 
-def test_config3_sweep_free_running_invariants():
-    """Config 3's sweep at full per-layer shape (M = B = 4096, E = 4), 6 of its 50 steps, free running
-    on the GPU: the cache is M after every step once filled and never exceeds M + B rows."""
+FOLDED_CASES = [
+    # (workload, sampled (item, head) pairs: first and last item, every head index, items on every XCD residue)
+    ("llama31_8b", [(0, 0), (1, 1), (17, 2), (42, 3), (64, 4), (99, 5), (126, 6), (127, 7)]),
+    ("qwen25_7b", [(0, 0), (1, 1), (50, 2), (77, 3), (111, 0), (150, 1), (222, 2), (223, 3)]),
+    ("stress", [(0, 0), (1, 1), (100, 2), (255, 3), (256, 5), (300, 6), (511, 4), (511, 7)]),
+]
+
+
+@pytest.mark.parametrize("name,samples", FOLDED_CASES, ids=[c[0] for c in FOLDED_CASES])
+def test_configs_3_to_5_all_layers_folded_as_benchmarked(name, samples):
+    """The launch bench.py times for the large workloads: all L layers x E episodes in one call
+    (stress: 512 caches x 8 KV heads of 24576 rows).  Properties over the whole batch on the device,
+    eight sampled heads against the oracle."""
+    w = synth.WORKLOADS[name]
+    reduce = orc.REDUCE_SUM
+    say(f"{name} folded L={w.L} x E={w.E} = {w.L * w.E} caches")
+    q, k0, v0 = synth.make_folded(w, range(w.L), device=DEV)
+    k, v = k0.clone(), v0.clone()
+    scores, keep = evict_on_gpu(q, k, v, w.M, w.N, reduce)
+    check_sampled(q, k0, v0, k, v, scores, keep, w.M, w.N, reduce, [], name)
+    del k, v, v0
+    differ, worst = check_heads_against_oracle(q, k0, scores, keep, w.M, w.N, reduce, samples, name)
+    say(f"  worst relative score error {worst:.2e}, kept-set differences inside the band {differ}")
+    del q, k0, scores, keep
+    torch.cuda.empty_cache()
+
+
+def sweep_block(w, step):
+    """Fresh queries and a fresh block of B rows for one step of the block-prefill sweep."""
+    return synth.make_layer(w, layer=0, step=step, device=DEV, n_ctx=w.B)
+
+
+def test_config3_sweep_all_50_steps_free_running():
+    """Config 3's sweep at full per-layer shape (M = B = 4096, E = 4), all 50 blocks, free running on the
+    GPU (Sec. 2.2, App. A.3): the cache holds min(M, tokens so far) rows after every step, never more than
+    M + B during one, kept rows stay in order and the compaction is the bit-exact gather of the kept list."""
     w = synth.WORKLOADS["llama31_8b"]
     cap = w.M + w.B
-    say("config 3 sweep, free running")
+    say("config 3 sweep, 50 steps, free running")
     kbuf = torch.zeros(w.E, w.Hkv, cap, w.d, dtype=torch.bfloat16, device=DEV)
     vbuf = torch.zeros_like(kbuf)
     n_cached = 0
-    for step in range(6):
-        q, bk, bv = synth.make_layer(w, layer=0, step=step, device=DEV, n_ctx=w.B)
+    for step in range(50):
+        q, bk, bv = sweep_block(w, step)
         assert n_cached + w.B <= cap
         kbuf[:, :, n_cached:n_cached + w.B] = bk
         vbuf[:, :, n_cached:n_cached + w.B] = bv
@@ -121,13 +171,86 @@ def test_config3_sweep_free_running_invariants():
         ep.epicache_evict_step(prm, q, kbuf, vbuf, ws, None, keep)
         torch.cuda.synchronize()
         n_keep = min(w.M, N)
-        assert (keep[:, :, 1:] > keep[:, :, :-1]).all() and keep.min() >= 0 and keep.max() < N
+        assert (keep[:, :, 1:] > keep[:, :, :-1]).all() and keep.min() >= 0 and keep.max() < N, step
         idx = keep.long().unsqueeze(-1).expand(-1, -1, -1, w.d)
-        assert torch.equal(torch.gather(k0, 2, idx).view(torch.int16), kbuf[:, :, :n_keep].view(torch.int16))
-        assert torch.equal(torch.gather(v0, 2, idx).view(torch.int16), vbuf[:, :, :n_keep].view(torch.int16))
+        assert torch.equal(torch.gather(k0, 2, idx).view(torch.int16), kbuf[:, :, :n_keep].view(torch.int16)), step
+        assert torch.equal(torch.gather(v0, 2, idx).view(torch.int16), vbuf[:, :, :n_keep].view(torch.int16)), step
+        if step > 0:  # tokens of the new block do get in, old ones do get evicted
+            assert (keep >= w.M).any(), step
         n_cached = n_keep
-        assert n_cached == min(w.M, N)
+        assert n_cached == min(w.M, (step + 1) * w.B)
     assert n_cached == w.M
+
+
+@pytest.mark.parametrize("reduce", [orc.REDUCE_SUM, orc.REDUCE_MAX], ids=["sum", "max"])
+def test_config3_sweep_all_50_steps_resynchronised(reduce):
+    """The same sweep with the oracle in the loop.  Four tracked heads (one per episode, different KV heads)
+    are carried by the oracle from step to step: before every step the GPU's cache rows of those heads are
+    overwritten with the oracle's compacted output of the step before, then the step's scores, kept set (band
+    rule) and compacted K/V are compared.  On steps 2, 25 and 50 every one of the 32 heads is compared, the
+    untracked ones from the GPU's own state before the step."""
+    w = synth.WORKLOADS["llama31_8b"]
+    cap, M, B, d = w.M + w.B, w.M, w.B, w.d
+    rtol = pu.RTOL_BF16
+    tracked = [(0, 0), (1, 3), (2, 5), (3, 7)]
+    G = w.G
+    say(f"config 3 sweep, 50 steps, resynchronised, reduce={reduce}")
+    kbuf = torch.zeros(w.E, w.Hkv, cap, d, dtype=torch.bfloat16, device=DEV)
+    vbuf = torch.zeros_like(kbuf)
+    state = {bh: (torch.empty(0, d, dtype=torch.bfloat16), torch.empty(0, d, dtype=torch.bfloat16)) for bh in tracked}
+    n_cached, differ_total, worst = 0, 0, 0.0
+    pool = ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1)))
+    for step in range(50):
+        q, bk, bv = sweep_block(w, step)
+        for (b, h) in tracked:  # resynchronise: the oracle's cache of this head replaces the GPU's
+            ok_, ov_ = state[(b, h)]
+            assert ok_.shape[0] == n_cached
+            kbuf[b, h, :n_cached] = ok_.to(DEV)
+            vbuf[b, h, :n_cached] = ov_.to(DEV)
+        kbuf[:, :, n_cached:n_cached + B] = bk
+        vbuf[:, :, n_cached:n_cached + B] = bv
+        N = n_cached + B
+        n_keep = min(M, N)
+        every_head = (step + 1) in (2, 25, 50)
+        k0, v0 = kbuf.clone(), vbuf.clone()
+        prm = ep.make_params(q, kbuf, n_cached=n_cached, n_block=B, budget=M, reduce=reduce)
+        ws = ep.alloc_workspace(prm)
+        scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+        keep = torch.full((w.E, w.Hkv, n_keep), -1, dtype=torch.int32, device=DEV)
+        ep.epicache_evict_step(prm, q, kbuf, vbuf, ws, scores, keep)
+        torch.cuda.synchronize()
+        idx = keep.long().unsqueeze(-1).expand(-1, -1, -1, d)
+        assert torch.equal(torch.gather(k0, 2, idx).view(torch.int16), kbuf[:, :, :n_keep].view(torch.int16)), step
+        assert torch.equal(torch.gather(v0, 2, idx).view(torch.int16), vbuf[:, :, :n_keep].view(torch.int16)), step
+        heads = [(b, h) for b in range(w.E) for h in range(w.Hkv)] if every_head else tracked
+        host = {}
+        for (b, h) in heads:
+            host[(b, h)] = (synth.to_f64_numpy(q[b:b + 1, h * G:(h + 1) * G]), synth.to_f64_numpy(k0[b:b + 1, h:h + 1, :N]),
+                            synth.raw_bits_numpy(k0[b:b + 1, h:h + 1, :N]), synth.raw_bits_numpy(v0[b:b + 1, h:h + 1, :N]))
+
+        def oracle_step(bh):
+            qq, kk, kb, vb = host[bh]
+            return orc.evict_step(qq, kk, None, N, M, reduce, k_bits=kb, v_bits=vb)
+
+        results = list(pool.map(oracle_step, heads))  # one oracle call per head, spread over host threads
+        for (b, h), (o_s, o_idx, o_k, o_v) in zip(heads, results):
+            what = f"sweep step {step + 1} b={b} h={h}"
+            worst = max(worst, pu.assert_scores_close(scores[b, h].cpu().numpy(), o_s[0, 0], rtol, what))
+            g_idx = keep[b, h].cpu().numpy()
+            differ = pu.assert_keep_matches(g_idx[None, None], o_s, M, rtol, what)
+            differ_total += differ
+            if differ == 0:  # same kept list: the compacted rows are the oracle's, bit for bit
+                assert (g_idx == o_idx[0, 0]).all(), what
+                assert (synth.raw_bits_numpy(kbuf[b, h, :n_keep]) == o_k[0, 0]).all(), what
+                assert (synth.raw_bits_numpy(vbuf[b, h, :n_keep]) == o_v[0, 0]).all(), what
+            if (b, h) in state:
+                state[(b, h)] = (torch.from_numpy(o_k[0, 0].view("int16").copy()).view(torch.bfloat16),
+                                 torch.from_numpy(o_v[0, 0].view("int16").copy()).view(torch.bfloat16))
+        n_cached = n_keep
+        if step % 10 == 9:
+            say(f"  step {step + 1}: worst relative score error so far {worst:.2e}, kept-set differences {differ_total}")
+    pool.shutdown()
+    assert n_cached == M
 
 
 @pytest.mark.parametrize("select,pooled", [(ep.SELECT_PER_HEAD, False), (ep.SELECT_POOLED, True)],
