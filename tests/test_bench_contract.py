@@ -30,7 +30,7 @@ def test_flags_of_the_contract_parse_and_defaults_hold():
     try:
         sys.argv = ["bench.py"]
         a = bench.parse()
-        assert (a.gpus, a.workload, a.reduce) == (1, "llama32_3b", "sum") and a.steps >= 1 and a.warmup >= 0
+        assert (a.gpus, a.workload, a.reduce) == (1, "stress", "sum") and a.steps >= 1 and a.warmup >= 0
         sys.argv = ["bench.py", "--gpus", "1", "--steps", "7", "--warmup", "2"]
         a = bench.parse()
         assert (a.gpus, a.steps, a.warmup) == (1, 7, 2)
