@@ -357,6 +357,96 @@ def score_causal_patch(q, k, n_ctx: int, reduce: int = REDUCE_MAX, scale: float 
 
 
 # ---------------------------------------------------------------------------------------------
+# Attention-based baselines of App. A.2: Eq. 1 with another choice of patched prompt, on the same
+# top-M / compaction back end.
+#
+# KVzip: the patch is a repetition instruction followed by the whole block, so p is about the
+# block size (thousands of query tokens per head).  Nothing else changes: its scores are score()
+# above with that long patch.  Every scoring row is normalised on its own, so the reduction over
+# the rows may be taken over any partition of the patch tokens into chunks and then over the
+# chunks; score_by_patch_chunks() writes that out and the pins check it against score().
+#
+# SnapKV: the patch is the window formed by the last w tokens of the block itself (w = 64 in the
+# paper).  Those tokens are part of the context: their keys sit in rows n_ctx-w .. n_ctx-1 of the
+# cache, and in the forward pass window token t attends causally to every earlier row and to the
+# window rows up to itself.
+# Readings where the paper is silent: only the rows before the window are scored (a window token's
+# weight on another window token is not an importance vote for itself); the window rows are always
+# retained, as in SnapKV's own design, so the M - w best of the earlier rows are kept next to them;
+# the budget must therefore be at least w.  If n_ctx <= M nothing is evicted.
+# ---------------------------------------------------------------------------------------------
+
+def score_by_patch_chunks(q, k, n_ctx: int, chunk: int, reduce: int = REDUCE_MAX,
+                          scale: float | None = None) -> np.ndarray:
+    """score() of a long patch (KVzip), evaluated `chunk` patch tokens at a time and combined with
+    the same reduction.  q [nb, Hq, p, d].  Returns float64 [nb, Hkv, n_ctx]."""
+    p = q.shape[2]
+    out = None
+    for t0 in range(0, p, chunk):
+        part = score(q[:, :, t0:t0 + chunk], k, n_ctx, reduce, scale)
+        if out is None:
+            out = part
+        else:
+            out = np.maximum(out, part) if reduce == REDUCE_MAX else out + part
+    return out
+
+
+def score_snapkv(q_window, k, n_ctx: int, reduce: int = REDUCE_MAX, scale: float | None = None) -> np.ndarray:
+    """Importance of the rows before the observation window, voted by the window's own queries.
+
+    q_window [nb, Hq, w, d]: query states of the last w context tokens; k [nb, Hkv, C >= n_ctx, d].
+    Window token t sits at row n_ctx - w + t and attends to rows 0 .. n_ctx - w + t (itself included).
+    Returns float64 [nb, Hkv, n_ctx - w].
+    """
+    nb, Hq, w, d = q_window.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    n_before = n_ctx - w
+    assert n_before >= 0
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty((nb, Hkv, n_before), dtype=np.float64)
+    for b in range(nb):
+        for h in range(Hkv):
+            votes = np.empty((G * w, n_before), dtype=np.float64)
+            for g in range(G):
+                for t in range(w):
+                    visible = np.asarray(k[b, h, :n_before + t + 1], dtype=np.float64)
+                    z = scale * (visible @ np.asarray(q_window[b, h * G + g, t], dtype=np.float64))
+                    e = np.exp(z - z.max())
+                    votes[g * w + t] = e[:n_before] / e.sum()
+            if n_before:
+                out[b, h] = votes.max(axis=0) if reduce == REDUCE_MAX else votes.sum(axis=0)
+    return out
+
+
+def evict_step_snapkv(q_window, k, v, n_ctx: int, M: int, reduce: int = REDUCE_MAX, scale=None,
+                      k_bits=None, v_bits=None):
+    """One eviction step with SnapKV's observation window as the patched prompt.
+
+    Keeps the window rows and the M - w best-scoring earlier rows (selection on the scores rounded
+    to float32, ties to the lower row), in their original order.
+    Returns (scores float64 [nb, Hkv, n_ctx - w], keep_idx int32 [nb, Hkv, min(M, n_ctx)], K', V').
+    """
+    nb, Hq, w, d = q_window.shape
+    Hkv = k.shape[1]
+    assert M >= w, "the budget must cover the observation window"
+    s = score_snapkv(q_window, k, n_ctx, reduce, scale)
+    n_keep = min(M, n_ctx)
+    idx = np.empty((nb, Hkv, n_keep), dtype=np.int32)
+    window_rows = np.arange(n_ctx - w, n_ctx, dtype=np.int32)
+    for b in range(nb):
+        for h in range(Hkv):
+            if n_ctx <= M:
+                idx[b, h] = np.arange(n_ctx, dtype=np.int32)
+            else:
+                idx[b, h] = np.concatenate([topk_1d(s[b, h].astype(np.float32), M - w), window_rows])
+    kk = compact(k if k_bits is None else k_bits, idx)
+    vv = compact(v if v_bits is None else v_bits, idx)
+    return s, idx, kk, vv
+
+
+# ---------------------------------------------------------------------------------------------
 # KeyDiff scoring (App. A.2, "KeyDiff"): an attention-free baseline that runs on the same
 # select / compact back end.  Per KV head the anchor is the average of the key states of all
 # context tokens; a token's score is minus the cosine similarity between its key and the anchor,
