@@ -252,6 +252,35 @@ EPICACHE_API int epicache_evict_step_attn(const epicache_params* params, const v
                                           void* out, float* scores_opt, int32_t* keep_idx_opt, void* workspace,
                                           size_t workspace_bytes, void* hip_stream);
 
+/* App. A.2 ("SnapKV" inside block prefill): Eq. 1 with the block's own last w = patch_len tokens, the
+ * observation window, as the patched prompt.  The window rows are the last w of the N = n_cached + n_block
+ * context rows of K and V; q_window [n_batch, n_q_heads, w, head_dim] holds their query states (strides
+ * q_stride_*).  Window token t sits at row N - w + t and attends to rows 0 .. N - w + t, itself included, as
+ * in the model's forward pass; only the N - w rows before the window are scored, the window rows are always
+ * retained, and the budget - w best earlier rows are kept next to them, in row order (the paper says no more
+ * than that the window is the patched prompt; keeping the window is SnapKV's own design).
+ * Requires budget > w whenever N > budget (else EPICACHE_ERR_INVALID_ARG) and params->causal_patch = 0 (the
+ * call applies the window's mask itself).
+ * Out: scores_opt [n_batch, n_kv_heads, N - w] (nothing if N <= w), keep_idx_opt [n_batch, n_kv_heads,
+ * min(budget, N)]; both may be NULL.  K, V compacted in place.  If N <= budget nothing is evicted. */
+EPICACHE_API int epicache_snapkv_workspace_size(const epicache_params* params, size_t* bytes_out);
+EPICACHE_API int epicache_evict_step_snapkv(const epicache_params* params, const void* q_window, void* k, void* v,
+                                            float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream);
+
+/* App. A.2 ("KVzip" inside block prefill): Eq. 1 with a repetition instruction followed by the whole block as
+ * the patched prompt, i.e. a patch of thousands of tokens per query head.  Same scores as epicache_score, but
+ * patch_len may be anything up to 2^20 (n_q_heads / n_kv_heads <= 4096): every scoring row is normalised on
+ * its own, so the patch tokens are scored 4096 / (n_q_heads / n_kv_heads) at a time and the chunks' score
+ * vectors are combined with `reduce`.  causal_patch must be 0.  Results, optional outputs and the N <= budget
+ * case of epicache_evict_step_kvzip as epicache_evict_step. */
+EPICACHE_API int epicache_kvzip_workspace_size(const epicache_params* params, size_t* bytes_out);
+EPICACHE_API int epicache_score_kvzip(const epicache_params* params, const void* q, const void* k, float* scores,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+EPICACHE_API int epicache_evict_step_kvzip(const epicache_params* params, const void* q, void* k, void* v,
+                                           float* scores_opt, int32_t* keep_idx_opt, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream);
+
 /* App. A.2 ("KeyDiff"): the attention-free baseline scorer, for the same epicache_topk /
  * epicache_compact (or *_ragged) back end.  Per (b, h): anchor = mean of the key states of the
  * context rows; scores[b,h,i] = -cos(K[b,h,i,:], anchor), so the keys that point away from the bulk

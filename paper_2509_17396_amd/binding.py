@@ -25,7 +25,8 @@ ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_evict_step_static", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
-    "epicache_evict_step_ragged", "epicache_score_keydiff", "epicache_patch_attention",
+    "epicache_evict_step_ragged", "epicache_snapkv_workspace_size", "epicache_evict_step_snapkv",
+    "epicache_kvzip_workspace_size", "epicache_score_kvzip", "epicache_evict_step_kvzip", "epicache_score_keydiff", "epicache_patch_attention",
     "epicache_patch_attention_ragged",
     "epicache_evict_step_attn",
     "epicache_episode_medoids", "epicache_match_queries", "epicache_status_string", "epicache_version",
@@ -100,6 +101,11 @@ def load() -> ctypes.CDLL:
     lib.epicache_select_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_snapkv_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.epicache_evict_step_snapkv.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_kvzip_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.epicache_score_kvzip.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_evict_step_kvzip.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_score_keydiff.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.epicache_patch_attention.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.epicache_patch_attention_ragged.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
@@ -257,6 +263,35 @@ def epicache_evict_step_attn(params: Params, q, k, v, out, workspace, scores=Non
     _check(load().epicache_evict_step_attn(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(scores),
                                            _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step_attn")
+
+
+def epicache_snapkv_workspace_size(params: Params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().epicache_snapkv_workspace_size(ctypes.byref(params), ctypes.byref(out)), "epicache_snapkv_workspace_size")
+    return out.value
+
+
+def epicache_evict_step_snapkv(params: Params, q_window, k, v, workspace, scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step_snapkv(ctypes.byref(params), _ptr(q_window), _ptr(k), _ptr(v), _ptr(scores),
+                                             _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
+           "epicache_evict_step_snapkv")
+
+
+def epicache_kvzip_workspace_size(params: Params) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().epicache_kvzip_workspace_size(ctypes.byref(params), ctypes.byref(out)), "epicache_kvzip_workspace_size")
+    return out.value
+
+
+def epicache_score_kvzip(params: Params, q, k, scores, workspace) -> None:
+    _check(load().epicache_score_kvzip(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(scores), _ptr(workspace),
+                                       workspace.numel(), _stream()), "epicache_score_kvzip")
+
+
+def epicache_evict_step_kvzip(params: Params, q, k, v, workspace, scores=None, keep_idx=None) -> None:
+    _check(load().epicache_evict_step_kvzip(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
+                                            _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
+           "epicache_evict_step_kvzip")
 
 
 def epicache_score_keydiff(params: Params, k, scores, workspace, n_ctx=None) -> None:

@@ -180,6 +180,117 @@ static int run_score_lse(const Plan& pl, const void* q, const void* k, const flo
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
 
+// ---- App. A.2 "SnapKV": the last w = patch_len context rows are the observation window.  The plan of the
+// scoring and selection inside: N - w rows scored under the causal mask of the window (its keys follow those
+// rows, which is the causal_patch layout), M - w of them kept.
+struct SnapkvPlan {
+  Plan outer;   // all N context rows, budget M: the compaction
+  Plan inner;   // the N - w rows before the window, budget M - w: scoring and selection
+  bool evicts;  // N > M
+  bool scores;  // there are rows before the window
+  size_t off_scores, off_keep, total;
+};
+
+static int make_snapkv_plan(const epicache_params* prm, SnapkvPlan* out) {
+  SnapkvPlan sp;
+  int st = make_plan(prm, &sp.outer);
+  if (st != EPICACHE_OK) return st;
+  if (prm->causal_patch) return EPICACHE_ERR_INVALID_ARG;  // the call applies the window's causal mask itself
+  const Plan& po = sp.outer;
+  const int w = po.p;
+  sp.evicts = po.N > po.M;
+  sp.scores = po.N > w;
+  if (sp.evicts && po.M <= w) return EPICACHE_ERR_INVALID_ARG;  // the budget must exceed the window it always keeps
+  const int64_t nbh = (int64_t)po.nb * po.Hkv;
+  if (sp.scores) {
+    epicache_params pi = *prm;
+    const int n_before = po.N - w;
+    pi.n_cached = prm->n_cached < n_before ? prm->n_cached : n_before;
+    pi.n_block = n_before - pi.n_cached;
+    pi.budget = sp.evicts ? po.M - w : po.M;
+    pi.causal_patch = 1;
+    st = make_plan(&pi, &sp.inner);
+    if (st != EPICACHE_OK) return st;
+    sp.off_scores = sp.inner.off_scores;
+    sp.off_keep = sp.inner.off_keep;
+  } else {
+    sp.inner = po;
+    sp.off_scores = sp.off_keep = 0;
+  }
+  sp.total = sp.off_keep + align256((size_t)nbh * po.n_keep * sizeof(int32_t));
+  *out = sp;
+  return EPICACHE_OK;
+}
+
+// ---- App. A.2 "KVzip": the patch is the whole block behind an instruction, thousands of tokens per query
+// head.  The patch tokens are scored kChunkRows / G at a time with the kernels of epicache_score and the chunk
+// results are combined with the reduction.
+constexpr int kLongPatchChunkRows = 4096;  // scoring rows (G x tokens) per chunk
+
+struct LongPatchPlan {
+  Plan body, tail;      // a full chunk of patch tokens; the last, shorter chunk (n_tail_tokens > 0)
+  Plan whole;           // N, M, n_keep of the step (taken from `body`)
+  int chunk_tokens, n_body, n_tail_tokens;
+  size_t off_tmp, off_scores, off_keep, total;
+};
+
+static int make_long_patch_plan(const epicache_params* prm, LongPatchPlan* out) {
+  if (!prm) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->struct_size != sizeof(epicache_params)) return EPICACHE_ERR_INVALID_ARG;
+  if (prm->patch_len < 1 || prm->n_q_heads < 1 || prm->n_kv_heads < 1 || prm->n_q_heads % prm->n_kv_heads != 0)
+    return EPICACHE_ERR_INVALID_ARG;
+  if (prm->causal_patch) return EPICACHE_ERR_INVALID_ARG;  // chunks would need the patch keys of earlier chunks
+  if (prm->patch_len > (1 << 20)) return EPICACHE_ERR_UNSUPPORTED;
+  const int G = prm->n_q_heads / prm->n_kv_heads;
+  LongPatchPlan lp;
+  int pc = kLongPatchChunkRows / G;
+  if (pc >= 64) pc = pc / 64 * 64;  // whole 64-row tiles inside one query head
+  if (pc < 1) pc = 1;
+  if (pc > prm->patch_len) pc = prm->patch_len;
+  lp.chunk_tokens = pc;
+  lp.n_body = prm->patch_len / pc;
+  lp.n_tail_tokens = prm->patch_len % pc;
+  // the strides must hold the whole patch, not just one chunk
+  if (prm->q_stride_t >= 0 && prm->q_stride_h < prm->q_stride_t * (int64_t)(prm->patch_len - 1) + prm->head_dim)
+    return EPICACHE_ERR_INVALID_ARG;
+  if (prm->n_batch > 1 && prm->q_stride_b < prm->q_stride_h * (int64_t)(prm->n_q_heads - 1) +
+                                                prm->q_stride_t * (int64_t)(prm->patch_len - 1) + prm->head_dim)
+    return EPICACHE_ERR_INVALID_ARG;
+  epicache_params pb = *prm;
+  pb.patch_len = pc;
+  int st = make_plan(&pb, &lp.body);
+  if (st != EPICACHE_OK) return st;
+  lp.tail = lp.body;
+  if (lp.n_tail_tokens) {
+    pb.patch_len = lp.n_tail_tokens;
+    st = make_plan(&pb, &lp.tail);
+    if (st != EPICACHE_OK) return st;
+  }
+  lp.whole = lp.body;
+  const int64_t nbh = (int64_t)lp.body.nb * lp.body.Hkv;
+  lp.off_tmp = lp.body.off_scores > lp.tail.off_scores ? lp.body.off_scores : lp.tail.off_scores;
+  lp.off_scores = lp.off_tmp + align256((size_t)nbh * lp.body.N * sizeof(float));
+  lp.off_keep = lp.off_scores + align256((size_t)nbh * lp.body.N * sizeof(float));
+  lp.total = lp.off_keep + align256((size_t)nbh * lp.body.n_keep * sizeof(int32_t));
+  *out = lp;
+  return EPICACHE_OK;
+}
+
+// scores of the whole patch: chunk 0 writes `scores`, every later chunk goes to `tmp` and is folded in
+static int run_score_long_patch(const LongPatchPlan& lp, const void* q, const void* k, float* scores, char* ws,
+                                hipStream_t stream) {
+  float* tmp = reinterpret_cast<float*>(ws + lp.off_tmp);
+  const int n_chunks = lp.n_body + (lp.n_tail_tokens ? 1 : 0);
+  for (int c = 0; c < n_chunks; c++) {
+    const Plan& pc = c < lp.n_body ? lp.body : lp.tail;
+    const char* qc = static_cast<const char*>(q) + (size_t)c * lp.chunk_tokens * pc.qst * pc.elem;
+    int st = run_score(pc, qc, k, c == 0 ? scores : tmp, ws, stream);
+    if (st != EPICACHE_OK) return st;
+    if (c > 0 && launch_combine_scores(lp.whole, scores, tmp, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  }
+  return EPICACHE_OK;
+}
+
 // Workspace of epicache_evict_step_static: one array per GPU, held from the moment the code object is
 // loaded until the process ends.  Host code never uses the array's name as an address: its device address
 // is looked up once per device (static_scratch) and that pointer is what the kernels receive.
@@ -422,6 +533,102 @@ int epicache_evict_step_lse(const epicache_params* params, const void* q, void* 
                             void* workspace, size_t workspace_bytes, void* hip_stream) {
   return evict_step_impl(params, q, k, v, row_lse, true, scores_opt, keep_idx_opt, workspace,
                          workspace_bytes, hip_stream);
+}
+
+int epicache_snapkv_workspace_size(const epicache_params* params, size_t* bytes_out) {
+  if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
+  SnapkvPlan sp;
+  int st = make_snapkv_plan(params, &sp);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = sp.total;
+  return EPICACHE_OK;
+}
+
+int epicache_evict_step_snapkv(const epicache_params* params, const void* q_window, void* k, void* v,
+                               float* scores_opt, int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  SnapkvPlan sp;
+  int st = make_snapkv_plan(params, &sp);
+  if (st != EPICACHE_OK) return st;
+  if (!q_window || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q_window) || misaligned(k) || misaligned(v) || misaligned(workspace) || misaligned(scores_opt) ||
+      misaligned(keep_idx_opt))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < sp.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + sp.off_scores);
+  int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + sp.off_keep);
+  const Plan& po = sp.outer;
+  if (!sp.evicts) {  // the cache is still filling up: everything stays
+    if (scores_opt && sp.scores) {
+      st = run_score(sp.inner, q_window, k, scores, ws, stream);
+      if (st != EPICACHE_OK) return st;
+    }
+    if (keep_idx_opt && launch_iota_keep(po, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  }
+  // N > M > w: score the rows before the window, keep the best M - w of them and the window itself
+  st = run_score(sp.inner, q_window, k, scores, ws, stream);
+  if (st != EPICACHE_OK) return st;
+  Plan sel = sp.inner;
+  sel.keep_stride = po.n_keep;  // the selection fills the first M - w entries of rows that are M long
+  if (launch_topk(sel, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  if (launch_append_rows(po, keep, po.M - po.p, po.p, po.N - po.p, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  if (launch_compact(po, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
+}
+
+int epicache_kvzip_workspace_size(const epicache_params* params, size_t* bytes_out) {
+  if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
+  LongPatchPlan lp;
+  int st = make_long_patch_plan(params, &lp);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = lp.total;
+  return EPICACHE_OK;
+}
+
+int epicache_score_kvzip(const epicache_params* params, const void* q, const void* k, float* scores,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  LongPatchPlan lp;
+  int st = make_long_patch_plan(params, &lp);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !scores || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(scores) || misaligned(workspace)) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < lp.off_scores) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  return run_score_long_patch(lp, q, k, scores, static_cast<char*>(workspace), (hipStream_t)hip_stream);
+}
+
+int epicache_evict_step_kvzip(const epicache_params* params, const void* q, void* k, void* v, float* scores_opt,
+                              int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  LongPatchPlan lp;
+  int st = make_long_patch_plan(params, &lp);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) || misaligned(scores_opt) ||
+      misaligned(keep_idx_opt))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < lp.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  float* scores = scores_opt ? scores_opt : reinterpret_cast<float*>(ws + lp.off_scores);
+  int32_t* keep = keep_idx_opt ? keep_idx_opt : reinterpret_cast<int32_t*>(ws + lp.off_keep);
+  const Plan& pw = lp.whole;
+  if (pw.N <= pw.M) {  // nothing to evict
+    if (scores_opt) {
+      st = run_score_long_patch(lp, q, k, scores, ws, stream);
+      if (st != EPICACHE_OK) return st;
+    }
+    if (keep_idx_opt && launch_iota_keep(pw, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  }
+  st = run_score_long_patch(lp, q, k, scores, ws, stream);
+  if (st != EPICACHE_OK) return st;
+  if (launch_topk(pw, scores, keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  if (launch_compact(pw, keep, k, v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+  return EPICACHE_OK;
 }
 
 int epicache_ragged_workspace_size(const epicache_params* params, int32_t select, size_t* bytes_out,

@@ -60,6 +60,10 @@ hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float
 hipError_t launch_lse_to_stats(const Plan& pl, const float* row_lse, float2* stats, hipStream_t stream);
 hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipStream_t stream);
 hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);
+// keep[bh][first + j] = row0 + j, j < count (rows of pitch pl.keep_stride): rows retained unconditionally
+hipError_t launch_append_rows(const Plan& pl, int32_t* keep, int first, int count, int row0, hipStream_t stream);
+// dst = reduce(dst, src) elementwise over [nb, Hkv, N] scores (pl.reduce)
+hipError_t launch_combine_scores(const Plan& pl, float* dst, const float* src, hipStream_t stream);
 hipError_t launch_compact(const Plan& pl, const int32_t* keep, void* k, void* v,
                           hipStream_t stream);
 size_t select_ragged_record_bytes(const Plan& pl);

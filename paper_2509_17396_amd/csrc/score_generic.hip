@@ -138,7 +138,26 @@ hipError_t launch_t(const Plan& pl, const T* q, const T* k, float* scores, float
   return hipGetLastError();
 }
 
+// dst[i] = reduce(dst[i], src[i]): the scores of two disjoint sets of scoring rows become those of their union
+// (every scoring row is normalised on its own, so a long patch can be scored in chunks of its tokens).
+template <int REDUCE>
+__global__ void combine_scores(float* __restrict__ dst, const float* __restrict__ src, size_t total) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = REDUCE == EPICACHE_REDUCE_MAX ? fmaxf(dst[i], src[i]) : dst[i] + src[i];
+}
+
 }  // namespace
+
+hipError_t launch_combine_scores(const Plan& pl, float* dst, const float* src, hipStream_t stream) {
+  const size_t total = (size_t)pl.nb * pl.Hkv * pl.N;
+  const size_t blocks = (total + 255) / 256;
+  const dim3 grid((unsigned)(blocks < (1u << 20) ? blocks : (1u << 20)));
+  if (pl.reduce == EPICACHE_REDUCE_MAX)
+    hipLaunchKernelGGL(combine_scores<EPICACHE_REDUCE_MAX>, grid, dim3(256), 0, stream, dst, src, total);
+  else
+    hipLaunchKernelGGL(combine_scores<EPICACHE_REDUCE_SUM>, grid, dim3(256), 0, stream, dst, src, total);
+  return hipGetLastError();
+}
 
 hipError_t launch_score_generic(const Plan& pl, const void* q, const void* k, float* scores,
                                 float2* stats, bool stats_ready, hipStream_t stream) {

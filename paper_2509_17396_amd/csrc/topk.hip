@@ -18,13 +18,14 @@ namespace {
 // VPT == 0: keys are re-read from global memory in every pass (any N).
 template <int VPT>
 __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ scores,
-                                                    int32_t* __restrict__ keep, int N, int n_keep) {
+                                                    int32_t* __restrict__ keep, int N, int n_keep,
+                                                    int pitch) {
   __shared__ uint32_t hist[4][256];
   __shared__ uint32_t wave_gt[16], wave_eq[16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nwaves = blockDim.x >> 6;
   const float* row = scores + (size_t)blockIdx.x * N;
-  int32_t* out = keep + (size_t)blockIdx.x * n_keep;
+  int32_t* out = keep + (size_t)blockIdx.x * pitch;  // rows of kept indices are `pitch` apart
 
   const int groups = VPT > 0 ? VPT : (N + nwaves * 64 - 1) / (nwaves * 64);  // 64-wide groups per wave
   const int base = wave * groups * 64 + lane;
@@ -117,7 +118,20 @@ __global__ void iota_keep(int32_t* keep, int n_keep, size_t total) {
   if (i < total) keep[i] = (int32_t)(i % n_keep);
 }
 
+// keep[bh][first + j] = row0 + j for j < count: rows that are retained whatever they score
+__global__ void append_rows(int32_t* keep, int pitch, int first, int count, int row0, size_t total) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) keep[(i / count) * pitch + first + (i % count)] = row0 + (int32_t)(i % count);
+}
+
 }  // namespace
+
+hipError_t launch_append_rows(const Plan& pl, int32_t* keep, int first, int count, int row0, hipStream_t stream) {
+  const size_t total = (size_t)pl.nb * pl.Hkv * count;
+  hipLaunchKernelGGL(append_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, keep,
+                     pl.keep_stride, first, count, row0, total);
+  return hipGetLastError();
+}
 
 hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream) {
   const size_t total = (size_t)pl.nb * pl.Hkv * pl.n_keep;
@@ -128,20 +142,20 @@ hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream) {
 
 hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipStream_t stream) {
   if (pl.N <= pl.M) return launch_iota_keep(pl, keep, stream);
-  const int nbh = pl.nb * pl.Hkv, N = pl.N, nk = pl.n_keep;
+  const int nbh = pl.nb * pl.Hkv, N = pl.N, nk = pl.n_keep, pitch = pl.keep_stride;
   dim3 grid(nbh);
   if (N <= 1024)
-    hipLaunchKernelGGL(topk_select<4>, grid, dim3(256), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<4>, grid, dim3(256), 0, stream, scores, keep, N, nk, pitch);
   else if (N <= 4096)
-    hipLaunchKernelGGL(topk_select<16>, grid, dim3(256), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<16>, grid, dim3(256), 0, stream, scores, keep, N, nk, pitch);
   else if (N <= 8192)
-    hipLaunchKernelGGL(topk_select<16>, grid, dim3(512), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<16>, grid, dim3(512), 0, stream, scores, keep, N, nk, pitch);
   else if (N <= 16384)
-    hipLaunchKernelGGL(topk_select<16>, grid, dim3(1024), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<16>, grid, dim3(1024), 0, stream, scores, keep, N, nk, pitch);
   else if (N <= 32768)
-    hipLaunchKernelGGL(topk_select<32>, grid, dim3(1024), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<32>, grid, dim3(1024), 0, stream, scores, keep, N, nk, pitch);
   else
-    hipLaunchKernelGGL(topk_select<0>, grid, dim3(1024), 0, stream, scores, keep, N, nk);
+    hipLaunchKernelGGL(topk_select<0>, grid, dim3(1024), 0, stream, scores, keep, N, nk, pitch);
   return hipGetLastError();
 }
 
