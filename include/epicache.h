@@ -36,6 +36,11 @@
  *     Anything else returns EPICACHE_ERR_UNSUPPORTED.
  *   - Calls that use the same workspace or the same K/V buffers must be ordered
  *     by the caller (same stream or events).
+ *   - One side effect outside the buffers: a bf16 scoring call with more than 8128
+ *     scoring rows per KV head (patch_len * n_q_heads / n_kv_heads) needs more than
+ *     the default 64 KB of dynamic LDS for one of its kernels and raises that
+ *     kernel's limit with hipFuncSetAttribute before the launch (process-wide for
+ *     that kernel on the current device, idempotent, not a stream operation).
  */
 #ifndef EPICACHE_H
 #define EPICACHE_H

@@ -12,6 +12,10 @@ namespace epicache {
 
 static size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Compute units of the one target of this build, MI355X (gfx950): 8 XCDs x 32.  It only steers the split
+// heuristic below (how many key splits fill whole rounds of resident workgroups); results never depend on it.
+constexpr int kComputeUnits = 256;
+
 // Number of key splits for a kernel whose grid is `base` workgroups per split: the split count
 // (at most 32, at least 4 key tiles each) whose workgroup count fills whole rounds of the `slots`
 // workgroups the chip holds at once; `penalty` per split favours fewer splits.
@@ -102,9 +106,9 @@ int make_plan(const epicache_params* prm, Plan* out) {
     else if (pl.R <= 128) pl.stats_rows_per_wg = 128;
     else pl.stats_rows_per_wg = ((pl.R + 191) / 192 * 192 < (pl.R + 255) / 256 * 256) ? 192 : 256;
     const int64_t base = nbh * ((pl.R + pl.stats_rows_per_wg - 1) / pl.stats_rows_per_wg);
-    // workgroups that fit the chip at once: 8 waves per CU (2 per SIMD), 256 CUs
+    // workgroups that fit the chip at once: 8 waves per CU (2 per SIMD)
     const int nw = pl.stats_rows_per_wg == 192 ? 2 : pl.stats_rows_per_wg == 64 ? 2 : pl.stats_rows_per_wg == 32 ? 1 : 4;
-    const int64_t slots = 256 * (8 / nw);
+    const int64_t slots = kComputeUnits * (8 / nw);
     pick_splits(base, slots, tiles, 0.004, &pl.n_splits, &pl.tiles_per_split);
     // the streaming reduction re-derives every row's log-sum-exp per workgroup: fewer, longer splits
     pick_splits(nbh, slots, tiles, 0.03, &pl.reduce_splits, &pl.reduce_tiles_per_split);

@@ -58,17 +58,18 @@ __global__ __launch_bounds__(kThreads) void episode_centroids(const float* __res
   float acc = 0.f;
   int count = 0;
   for (int k0 = 0; k0 < K; k0 += kRowsInFlight) {
-    float x[kRowsInFlight], m[kRowsInFlight];
+    float x[kRowsInFlight];
+    bool m[kRowsInFlight];
 #pragma unroll
     for (int u = 0; u < kRowsInFlight; u++) {
       const int k = k0 + u < K ? k0 + u : K - 1;
       x[u] = col[(size_t)k * D];
       const bool mine = k0 + u < K && assign[k] == e;
-      m[u] = mine ? 1.f : 0.f;
+      m[u] = mine;
       count += mine;
     }
 #pragma unroll
-    for (int u = 0; u < kRowsInFlight; u++) acc = fmaf(m[u], x[u], acc);
+    for (int u = 0; u < kRowsInFlight; u++) acc += m[u] ? x[u] : 0.f;  // a select: a non-finite row of another cluster cannot leak in
   }
   if (own) centroids[(size_t)e * D + d] = count ? acc / (float)count : 0.f;
 }

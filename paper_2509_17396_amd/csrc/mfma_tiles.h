@@ -55,18 +55,24 @@ struct Tile {
 // writes LDS bytes [lds_addr + 16*l, +16).  Issued as inline assembly so that the compiler's
 // wait-count pass does not serialise later ds_reads of the *other* LDS buffer behind these loads;
 // completion is awaited explicitly (wait_vmem) before the barrier that publishes the tile.
+// M0 is on the clobber lists: the statements overwrite it, and the compiler (which sets M0 itself right before
+// its own users of it) must not assume a value survives them.  Clang flags any reserved register on a clobber
+// list; for M0 the entry is exactly the definition that has to be declared.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16_uniform_base(uint32_t lds_addr, const void* base, uint32_t voff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_addr), "v"(voff), "s"(base)
-               : "memory");
+               : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_lane_ptr(uint32_t lds_addr, const void* ptr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :
                : "s"(lds_addr), "v"(ptr)
-               : "memory");
+               : "memory", "m0");
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)LDS_PTR(p);
 }

@@ -108,3 +108,20 @@ def test_matching_ties_zero_vectors_and_threshold_edge():
     got, _ = gpu_match(q, cents, 1.0)        # cosine == tau still matches (only "below" opens an episode)
     assert got.tolist() == [0, -1, -1, -1] or got.tolist() == [0, 4, -1, -1]
     assert orc.match_queries(q, cents, 1.0)[0][0] == 0
+
+
+def test_centroid_depends_on_its_members_only():
+    """Eq. 3: a centroid is the mean of its own members.  A non-finite embedding in one cluster must not
+    reach the centroids of the others."""
+    say("centroids with a non-finite member elsewhere")
+    emb, assign = clustered(3, 300, 256, 4)
+    bad = int(np.nonzero(assign == 2)[0][0])
+    emb[bad, 5], emb[bad, 17] = np.inf, np.nan
+    cent, _ = gpu_medoids(emb, assign, 4)
+    clean = emb.copy()
+    clean[bad] = 0.0
+    o_cent, _ = orc.episode_medoids(clean, assign, 4)
+    for e in (0, 1, 3):
+        assert np.isfinite(cent[e]).all()
+        np.testing.assert_allclose(cent[e], o_cent[e], rtol=1e-5, atol=1e-6)
+    assert not np.isfinite(cent[2, 5]) and not np.isfinite(cent[2, 17])
