@@ -122,6 +122,8 @@ int make_plan(const epicache_params* prm, Plan* out) {
   size_t off = 0;
   pl.off_stats = off;
   off += align256((size_t)nbh * pl.n_splits * pl.Rpad * sizeof(float2));
+  pl.off_nlse = off;  // one combined normaliser per scoring row, between the two scoring passes
+  off += align256((size_t)nbh * pl.Rpad * sizeof(float));
   pl.off_scores = off;
   off += align256((size_t)nbh * pl.N * sizeof(float));
   pl.off_keep = off;
@@ -167,7 +169,8 @@ static bool misaligned(const void* ptr) { return (reinterpret_cast<uintptr_t>(pt
 static int run_score(const Plan& pl, const void* q, const void* k, float* scores, char* ws,
                      hipStream_t stream) {
   float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
-  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, false, stream)
+  float* nlse = reinterpret_cast<float*>(ws + pl.off_nlse);
+  hipError_t e = pl.use_mfma ? launch_score_mfma(pl, q, k, scores, stats, nlse, false, stream)
                              : launch_score_generic(pl, q, k, scores, stats, false, stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }
@@ -179,7 +182,8 @@ static int run_score_lse(const Plan& pl, const void* q, const void* k, const flo
   p1.n_splits = 1;
   float2* stats = reinterpret_cast<float2*>(ws + pl.off_stats);
   if (launch_lse_to_stats(p1, row_lse, stats, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
-  hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, true, stream)
+  float* nlse = reinterpret_cast<float*>(ws + pl.off_nlse);
+  hipError_t e = p1.use_mfma ? launch_score_mfma(p1, q, k, scores, stats, nlse, true, stream)
                              : launch_score_generic(p1, q, k, scores, stats, true, stream);
   return e == hipSuccess ? EPICACHE_OK : EPICACHE_ERR_DEVICE;
 }

@@ -31,7 +31,7 @@ struct Plan {
   int reduce_splits;  // key splits of the streaming reduction pass
   int reduce_tiles_per_split;
   // workspace layout (byte offsets, 256-aligned)
-  size_t off_stats, off_scores, off_keep, off_lse, ws_total;
+  size_t off_stats, off_nlse, off_scores, off_keep, off_lse, ws_total;
   // ragged batches: device arrays indexed by b * Hkv + h, null in the uniform calls
   const int32_t* n_ctx;   // context rows per (b, h), at most N; N is then the pitch of a score row
   const int32_t* n_kept;  // rows kept per (b, h), read by the compaction
@@ -55,8 +55,9 @@ int make_plan(const epicache_params* prm, Plan* out);
 // `stats_ready`: the row statistics are already in `stats` (one split); only the reduction pass runs.
 hipError_t launch_score_generic(const Plan& pl, const void* q, const void* k, float* scores,
                                 float2* stats, bool stats_ready, hipStream_t stream);
+// `nlse` [nb * Hkv, Rpad]: minus the base-2 log-sum-exp of every scoring row, written between the two passes
 hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float* scores,
-                             float2* stats, bool stats_ready, hipStream_t stream);
+                             float2* stats, float* nlse, bool stats_ready, hipStream_t stream);
 hipError_t launch_lse_to_stats(const Plan& pl, const float* row_lse, float2* stats, hipStream_t stream);
 hipError_t launch_topk(const Plan& pl, const float* scores, int32_t* keep, hipStream_t stream);
 hipError_t launch_iota_keep(const Plan& pl, int32_t* keep, hipStream_t stream);

@@ -342,6 +342,32 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   }
 }
 
+// ------------------------------------------------------- between the passes
+// The key splits of pass 1 become one number per scoring row: minus the base-2 log-sum-exp, which is what pass 2
+// adds to every scaled logit.  Done once per row here, not once per workgroup of pass 2: a head has up to a
+// hundred such workgroups, and a dependent chain of small loads at the start of each cost them a fifth of their
+// lifetime.  Rows beyond R get -inf (weight 0).
+__global__ void combine_row_stats(const float2* __restrict__ stats, float* __restrict__ nlse, int n_splits,
+                                  int R, int Rpad, size_t total) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const size_t bh = i / Rpad;
+  const int r = (int)(i % Rpad);
+  float val = -INFINITY;
+  if (r < R) {
+    const float2* st = stats + bh * n_splits * Rpad + r;
+    float mx = st[0].x;
+    for (int s = 1; s < n_splits; s++) mx = fmaxf(mx, st[(size_t)s * Rpad].x);
+    float den = 0.f;
+    for (int s = 0; s < n_splits; s++) {
+      const float2 e = st[(size_t)s * Rpad];
+      den += e.y * ex2(e.x - mx);
+    }
+    val = -(mx + __log2f(den));
+  }
+  nlse[i] = val;
+}
+
 // ------------------------------------------------------------------ pass 2
 // Column reduction of the previous accumulator tile (16 query rows of one key),
 // sliced like the statistics above.  nl[v] = -(base-2 lse) of the value's row.
@@ -426,7 +452,7 @@ __device__ __forceinline__ void read_nlse(float (&nl)[16], const float* nlse, in
 template <int HD, int REDUCE>
 __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict__ q,
                                                        const bf16_t* __restrict__ k,
-                                                       const float2* __restrict__ stats,
+                                                       const float* __restrict__ nlse_rows,
                                                        float* __restrict__ scores, Plan pl) {
   using TL = Tile<HD>;
   constexpr int KS = TL::kSteps;
@@ -472,21 +498,12 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   };
   stage_queries(lds0, 0);
 
-  // combine the key splits of pass 1 into one log-sum-exp per query row
-  for (int r = tid; r < pl.Rpad + 64; r += 256) {
-    float val = -INFINITY;
-    if (r < pl.R) {
-      const float2* st = stats + (size_t)bh * pl.n_splits * pl.Rpad + r;
-      float mx = st[0].x;
-      for (int s = 1; s < pl.n_splits; s++) mx = fmaxf(mx, st[(size_t)s * pl.Rpad].x);
-      float den = 0.f;
-      for (int s = 0; s < pl.n_splits; s++) {
-        const float2 e = st[(size_t)s * pl.Rpad];
-        den += e.y * ex2(e.x - mx);
-      }
-      val = -(mx + __log2f(den));
-    }
-    nlse[r] = val;
+  // minus the base-2 log-sum-exp of every query row of this head, then 64 rows of -inf (the "tile before the first")
+  {
+    const float4* src = reinterpret_cast<const float4*>(nlse_rows + (size_t)bh * pl.Rpad);
+    for (int r4 = tid; r4 < (pl.Rpad + 64) / 4; r4 += 256)
+      reinterpret_cast<float4*>(nlse)[r4] =
+          r4 < pl.Rpad / 4 ? src[r4] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
   }
 
   // key fragments of this wave stay in registers for the whole query loop
@@ -570,7 +587,7 @@ __device__ __forceinline__ void col_fold(const f32x16& P, const float (&nl)[16],
 template <int HD, int NQ, int NW, int REDUCE>
 __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_stream(const bf16_t* __restrict__ q,
                                                                   const bf16_t* __restrict__ k,
-                                                                  const float2* __restrict__ stats,
+                                                                  const float* __restrict__ nlse_rows,
                                                                   float* __restrict__ scores, Plan pl) {
   using TL = Tile<HD>;
   using ST = Stager<HD, NW>;
@@ -609,22 +626,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
   };
   stage_keys(lds0, t_begin);
 
-  // combine the key splits of pass 1 into minus one base-2 log-sum-exp per query row
-  for (int r = tid; r < kRows; r += NW * 64) {
-    float val = -INFINITY;  // rows beyond R: weight exp2(-inf) = 0
-    if (r < pl.R) {
-      const float2* st = stats + (size_t)bh * pl.n_splits * pl.Rpad + r;
-      float mx = st[0].x;
-      for (int s = 1; s < pl.n_splits; s++) mx = fmaxf(mx, st[(size_t)s * pl.Rpad].x);
-      float den = 0.f;
-      for (int s = 0; s < pl.n_splits; s++) {
-        const float2 e = st[(size_t)s * pl.Rpad];
-        den += e.y * ex2(e.x - mx);
-      }
-      val = -(mx + __log2f(den));
-    }
-    nlse[r] = val;
-  }
+  // minus the base-2 log-sum-exp of this head's query rows; rows beyond R: weight exp2(-inf) = 0
+  for (int r = tid; r < kRows; r += NW * 64)
+    nlse[r] = r < pl.Rpad ? nlse_rows[(size_t)bh * pl.Rpad + r] : -INFINITY;
 
   // query fragments (A operand: rows = queries) stay in registers for the whole key loop
   bf16x8 qf[NQ][KS];
@@ -722,15 +726,15 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_reduce_strea
 }
 
 template <int HD, int NQ, int NW>
-void launch_reduce_stream(const Plan& pl, const bf16_t* q, const bf16_t* k, const float2* stats,
+void launch_reduce_stream(const Plan& pl, const bf16_t* q, const bf16_t* k, const float* nlse,
                           float* scores, hipStream_t stream) {
   dim3 grid(pl.reduce_splits, pl.nb * pl.Hkv);
   if (pl.reduce == EPICACHE_REDUCE_MAX)
     hipLaunchKernelGGL((score_reduce_stream<HD, NQ, NW, EPICACHE_REDUCE_MAX>), grid, dim3(NW * 64), 0,
-                       stream, q, k, stats, scores, pl);
+                       stream, q, k, nlse, scores, pl);
   else
     hipLaunchKernelGGL((score_reduce_stream<HD, NQ, NW, EPICACHE_REDUCE_SUM>), grid, dim3(NW * 64), 0,
-                       stream, q, k, stats, scores, pl);
+                       stream, q, k, nlse, scores, pl);
 }
 
 template <int HD, int NQ, int NW>
@@ -744,7 +748,7 @@ void launch_stats(const Plan& pl, const bf16_t* q, const bf16_t* k, float2* stat
 
 template <int HD>
 hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* scores,
-                     float2* stats, bool stats_ready, hipStream_t stream) {
+                     float2* stats, float* nlse, bool stats_ready, hipStream_t stream) {
   using TL = Tile<HD>;
   const int nbh = pl.nb * pl.Hkv;
   if (!stats_ready) switch (pl.stats_rows_per_wg) {
@@ -754,13 +758,18 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
     case 64: launch_stats<HD, 1, 2>(pl, q, k, stats, stream); break;
     default: launch_stats<HD, 1, 1>(pl, q, k, stats, stream); break;
   }
+  {
+    const size_t total = (size_t)nbh * pl.Rpad;
+    hipLaunchKernelGGL(combine_row_stats, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, stats, nlse,
+                       pl.n_splits, pl.R, pl.Rpad, total);
+  }
   if (pl.R <= pl.stats_rows_per_wg) {
     switch (pl.stats_rows_per_wg) {
-      case 256: launch_reduce_stream<HD, 2, 4>(pl, q, k, stats, scores, stream); break;
-      case 192: launch_reduce_stream<HD, 3, 2>(pl, q, k, stats, scores, stream); break;
-      case 128: launch_reduce_stream<HD, 1, 4>(pl, q, k, stats, scores, stream); break;
-      case 64: launch_reduce_stream<HD, 1, 2>(pl, q, k, stats, scores, stream); break;
-      default: launch_reduce_stream<HD, 1, 1>(pl, q, k, stats, scores, stream); break;
+      case 256: launch_reduce_stream<HD, 2, 4>(pl, q, k, nlse, scores, stream); break;
+      case 192: launch_reduce_stream<HD, 3, 2>(pl, q, k, nlse, scores, stream); break;
+      case 128: launch_reduce_stream<HD, 1, 4>(pl, q, k, nlse, scores, stream); break;
+      case 64: launch_reduce_stream<HD, 1, 2>(pl, q, k, nlse, scores, stream); break;
+      default: launch_reduce_stream<HD, 1, 1>(pl, q, k, nlse, scores, stream); break;
     }
     return hipGetLastError();
   }
@@ -773,7 +782,7 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kernel, g2, dim3(256), smem, stream, q, k, stats, scores, pl);
+    hipLaunchKernelGGL(kernel, g2, dim3(256), smem, stream, q, k, nlse, scores, pl);
     return hipGetLastError();
   };
   if (pl.reduce == EPICACHE_REDUCE_MAX) return launch(score_reduce<HD, EPICACHE_REDUCE_MAX>);
@@ -783,11 +792,11 @@ hipError_t launch_hd(const Plan& pl, const bf16_t* q, const bf16_t* k, float* sc
 }  // namespace
 
 hipError_t launch_score_mfma(const Plan& pl, const void* q, const void* k, float* scores,
-                             float2* stats, bool stats_ready, hipStream_t stream) {
+                             float2* stats, float* nlse, bool stats_ready, hipStream_t stream) {
   const bf16_t* qq = static_cast<const bf16_t*>(q);
   const bf16_t* kk = static_cast<const bf16_t*>(k);
-  if (pl.d == 128) return launch_hd<128>(pl, qq, kk, scores, stats, stats_ready, stream);
-  if (pl.d == 64) return launch_hd<64>(pl, qq, kk, scores, stats, stats_ready, stream);
+  if (pl.d == 128) return launch_hd<128>(pl, qq, kk, scores, stats, nlse, stats_ready, stream);
+  if (pl.d == 64) return launch_hd<64>(pl, qq, kk, scores, stats, nlse, stats_ready, stream);
   return hipErrorInvalidValue;
 }
 
