@@ -34,5 +34,23 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_microbench(verbose: bool = False):
+    """Compile the stand-alone microbenchmarks under csrc/microbench (not part of the library)."""
+    outdir = os.path.join(PKG, "lib", "microbench")
+    os.makedirs(outdir, exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    built = []
+    for src in sorted(glob.glob(os.path.join(PKG, "csrc", "microbench", "*.hip"))):
+        exe = os.path.join(outdir, os.path.splitext(os.path.basename(src))[0])
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-w", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", "-o", exe, src]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        built.append(exe)
+    return built
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print("\n".join(build_microbench(verbose=True)))
