@@ -83,3 +83,35 @@ def test_broken_geometries_are_rejected(g, field, delta):
     size = ctypes.c_size_t(0)
     status = ep.load().epicache_workspace_size(ctypes.byref(prm), ctypes.byref(size))
     assert status in (ep.ERR_INVALID_ARG, ep.ERR_UNSUPPORTED), (g, field, delta, status)
+
+
+@settings(max_examples=300, deadline=None)
+@given(geometry)
+def test_snapkv_and_kvzip_plans_never_crash_and_follow_their_rules(g):
+    nb, Hkv, G, p, d, n_cached, n_block, budget, dtype, reduce, causal, extra, pad = g
+    prm = _dense_params(*g)
+    lib = ep.load()
+    N, R = n_cached + n_block, G * p
+    size = ctypes.c_size_t(0)
+    plain = lib.epicache_workspace_size(ctypes.byref(prm), ctypes.byref(size))
+    # SnapKV: the window (p rows) is part of the N context rows
+    st_s = lib.epicache_snapkv_workspace_size(ctypes.byref(prm), ctypes.byref(size))
+    if plain != ep.OK:
+        assert st_s == plain
+    elif causal:
+        assert st_s == ep.ERR_INVALID_ARG          # the call applies the window's mask itself
+    elif N > budget and budget <= p:
+        assert st_s == ep.ERR_INVALID_ARG          # the window alone would use up the budget
+    else:
+        # the window rows follow the rows that are scored: the same capacity as the plain step
+        assert st_s == ep.OK, (g, st_s)
+        assert size.value % 256 == 0 and size.value >= nb * Hkv * min(budget, N) * 4
+    # KVzip: any patch length; the same answer as the plain call where that accepts the patch
+    st_k = lib.epicache_kvzip_workspace_size(ctypes.byref(prm), ctypes.byref(size))
+    if N < 1:
+        assert st_k == ep.ERR_INVALID_ARG
+    elif causal:
+        assert st_k == ep.ERR_INVALID_ARG
+    else:
+        assert st_k == ep.OK, (g, st_k)
+        assert size.value % 256 == 0 and size.value >= 2 * nb * Hkv * N * 4 + nb * Hkv * min(budget, N) * 4
