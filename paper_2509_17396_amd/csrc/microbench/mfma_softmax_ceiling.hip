@@ -3,7 +3,9 @@
 // triples of plain vector work behind each MFMA; operands live in registers, there is no memory or LDS traffic,
 // nothing waits on anything.  The scoring passes (Sec. 2.3, Eq. 1) issue 8 MFMAs and 16 such triples per 32x32
 // tile of logits at head_dim 128, i.e. the "+ 2" line.  Operands are random bf16 values (all-zero operands draw
-// less power and run faster; last line).
+// less power and run faster; last line).  One more variant takes the row sums through the matrix core instead of
+// the vector adds: the weights are packed to bf16 and every fourth MFMA is followed by one product with a
+// constant operand (2 extra MFMAs per 8), which is slower than the adds it replaces.
 // Build and run:  hipcc --offload-arch=gfx950 -O3 -std=c++17 -w -Xclang -target-feature -Xclang -packed-fp32-ops
 //                 mfma_softmax_ceiling.hip -o mfma_softmax_ceiling && ./mfma_softmax_ceiling
 #include <hip/hip_runtime.h>
@@ -19,12 +21,30 @@ __global__ __launch_bounds__(256) void k(const uint4* in, float* out, unsigned l
   f32x16 c[NACC];
   for (int i = 0; i < NACC; i++) for (int v = 0; v < 16; v++) c[i][v] = 0.f;
   float x[16];
+  unsigned pk[4] = {0, 0, 0, 0};
+  f32x16 ones_acc = {0};
   for (int v = 0; v < 16; v++) x[v] = threadIdx.x * 1e-3f + v;
   unsigned long long t0 = __builtin_readcyclecounter();
   for (int it = 0; it < ITERS; it++) {
 #pragma unroll
     for (int i = 0; i < NACC; i++) {
       c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[i], 0, 0, 0);
+      if (VALU == 12) {
+#pragma unroll
+        for (int v = 0; v < 2; v++) {
+          const int j = (i * 2 + v) & 15;
+          x[j] = __builtin_amdgcn_exp2f(fmaf(x[j], 0.999f, -0.001f));
+        }
+        typedef __attribute__((ext_vector_type(2))) float f2;
+        typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+        const f2 pr = {x[(i * 2) & 15], x[(i * 2 + 1) & 15]};
+        pk[i & 3] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, b2));
+        if ((i & 3) == 3) {
+          typedef __attribute__((ext_vector_type(4))) unsigned u4;
+          const u4 w = {pk[0], pk[1], pk[2], pk[3]};
+          ones_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, w), ones_acc, 0, 0, 0);
+        }
+      } else
 #pragma unroll
       for (int v = 0; v < VALU; v++) {
         const int j = (i * VALU + v) & 15;
@@ -35,7 +55,7 @@ __global__ __launch_bounds__(256) void k(const uint4* in, float* out, unsigned l
   unsigned long long t1 = __builtin_readcyclecounter();
   float s = 0.f;
   for (int i = 0; i < NACC; i++) for (int v = 0; v < 16; v++) s += c[i][v];
-  for (int v = 0; v < 16; v++) s += x[v];
+  for (int v = 0; v < 16; v++) s += x[v] + ones_acc[v];
   out[blockIdx.x * 256 + threadIdx.x] = s;
   if (threadIdx.x == 0 && blockIdx.x == 0) cyc[0] = t1 - t0;
 }
@@ -71,6 +91,7 @@ int main() {
     run<8, 1>("MFMA + 1 (fma, exp2, add) each", wps, in, out, cyc);
     run<8, 2>("MFMA + 2 (fma, exp2, add) each", wps, in, out, cyc);
     run<8, 3>("MFMA + 3 (fma, exp2, add) each", wps, in, out, cyc);
+    run<8, 12>("MFMA + 2 (fma, exp2) + cvt_pk, +1 MFMA per 4", wps, in, out, cyc);
   }
   (void)hipMemset(in, 0, 16 * 128);
   run<8, 0>("MFMA only, 8 accumulators, zero operands", 2, in, out, cyc);
