@@ -5,7 +5,8 @@
 // tile of logits at head_dim 128, i.e. the "+ 2" line.  Operands are random bf16 values (all-zero operands draw
 // less power and run faster; last line).  One more variant takes the row sums through the matrix core instead of
 // the vector adds: the weights are packed to bf16 and every fourth MFMA is followed by one product with a
-// constant operand (2 extra MFMAs per 8), which is slower than the adds it replaces.
+// constant operand (2 extra MFMAs per 8), which is slower than the adds it replaces; another drops the multiply-add in
+// front of the exp2 and pays one extra MFMA per 8 (scale and reference folded into the contraction): no faster.
 // Build and run:  hipcc --offload-arch=gfx950 -O3 -std=c++17 -w -Xclang -target-feature -Xclang -packed-fp32-ops
 //                 mfma_softmax_ceiling.hip -o mfma_softmax_ceiling && ./mfma_softmax_ceiling
 #include <hip/hip_runtime.h>
@@ -29,7 +30,15 @@ __global__ __launch_bounds__(256) void k(const uint4* in, float* out, unsigned l
 #pragma unroll
     for (int i = 0; i < NACC; i++) {
       c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[i], 0, 0, 0);
-      if (VALU == 12) {
+      if (VALU == 21) {   // same without the multiply at all
+#pragma unroll
+        for (int v = 0; v < 2; v++) {
+          const int j = (i * 2 + v) & 15;
+          x[j] = __builtin_amdgcn_exp2f(x[j]);
+          x[(j + 5) & 15] = x[(j + 5) & 15] * 0.5f + x[j];
+        }
+        if ((i & 7) == 7) ones_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, ones_acc, 0, 0, 0);
+      } else if (VALU == 12) {
 #pragma unroll
         for (int v = 0; v < 2; v++) {
           const int j = (i * 2 + v) & 15;
@@ -92,6 +101,7 @@ int main() {
     run<8, 2>("MFMA + 2 (fma, exp2, add) each", wps, in, out, cyc);
     run<8, 3>("MFMA + 3 (fma, exp2, add) each", wps, in, out, cyc);
     run<8, 12>("MFMA + 2 (fma, exp2) + cvt_pk, +1 MFMA per 4", wps, in, out, cyc);
+    run<8, 21>("MFMA + 2 (exp2, fma-accumulate), +1 MFMA per 8", wps, in, out, cyc);
   }
   (void)hipMemset(in, 0, 16 * 128);
   run<8, 0>("MFMA only, 8 accumulators, zero operands", 2, in, out, cyc);
