@@ -139,9 +139,11 @@ __device__ __forceinline__ void stats_slot(f32x16& acc, const bf16x8 (&a)[KS], c
 
 __device__ __forceinline__ void stats_fold(const f32x16& P, RowStat& st, float c2);
 
-template <int KS>
+// DEFER: the sum is taken as it is and only its running maximum over several units is kept in `worst`; the
+// caller checks that once per key tile and, if it ever exceeded kRebase, redoes those units on the exact path.
+template <int KS, bool DEFER = false>
 __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], const bf16x8 (&b)[KS],
-                                           const f32x16& P, RowStat& st, float c2) {
+                                           const f32x16& P, RowStat& st, float c2, float* worst = nullptr) {
   using SL = Slots<KS>;
   float s0 = 0.f, s1 = 0.f, x[16];
   const float nmc = -st.m * c2;
@@ -160,8 +162,13 @@ __device__ __forceinline__ void stats_unit(f32x16& acc, const bf16x8 (&a)[KS], c
   stage_add<SL::reduce[KS - 2], SL::reduce[KS - 1]>(x, s0, s1);
   stage_add<SL::reduce[KS - 1], SL::reduce[KS]>(x, s0, s1);
   const float D = st.D + (s0 + s1);
-  if (__any(!(D <= kRebase))) stats_fold(P, st, c2);  // some row needs a new reference: exact path for the wave
-  else st.D = D;
+  if constexpr (DEFER) {
+    st.D = D;  // +inf at worst (a row without a reference, or a logit 2^60 in weight above it): never NaN
+    *worst = fmaxf(*worst, D);
+  } else {
+    if (__any(!(D <= kRebase))) stats_fold(P, st, c2);  // some row needs a new reference: exact path for the wave
+    else st.D = D;
+  }
   fence_sched();
 }
 
@@ -183,6 +190,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
   using TL = Tile<HD>;
   using ST = Stager<HD, NW>;
   constexpr int KS = TL::kSteps;
+  // the per-unit check of the running sums is deferred to once per tile where the registers allow it (the
+  // three-sub-tile form sits at the 256-register limit as it is)
+  constexpr bool kDeferCheck = NQ <= 2;
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * TL::kTileBytes];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -259,12 +269,41 @@ __global__ __launch_bounds__(NW * 64, (NW == 1 ? 1 : 2)) void score_stats(const 
     if (active) {
       bf16x8 kf[KS];  // one 32-key half at a time, refilled once its last MFMA has been issued
       read_frags<HD>(kf, cur, 0, l32, hi);
+      if constexpr (kDeferCheck) {
+        // The unit carried over from the previous tile is folded with its check at once (its keys are gone from
+        // LDS).  The tile's own units 0 .. 2*NQ-2 are folded unchecked; one look at their largest sum decides
+        // whether they are redone, from the row statistics as they were before them, on the exact path.  The
+        // tile is still in LDS then, and neither kf nor accA is live any more.
+        stats_unit<KS>(accA, kf, qf[0], accB, st[NQ - 1], c2);
+        RowStat before[NQ];
 #pragma unroll
-      for (int u = 0; u < 2 * NQ; u++) {
-        const int s = u % NQ, sp = (u + NQ * 2 - 1) % NQ;
-        if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
-        if (u & 1) stats_unit<KS>(accB, kf, qf[s], accA, st[sp], c2);
-        else       stats_unit<KS>(accA, kf, qf[s], accB, st[sp], c2);
+        for (int s = 0; s < NQ; s++) before[s] = st[s];
+        float worst = 0.f;
+#pragma unroll
+        for (int u = 1; u < 2 * NQ; u++) {
+          const int s = u % NQ, sp = (u - 1) % NQ;
+          if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
+          if (u & 1) stats_unit<KS, true>(accB, kf, qf[s], accA, st[sp], c2, &worst);
+          else       stats_unit<KS, true>(accA, kf, qf[s], accB, st[sp], c2, &worst);
+        }
+        if (__any(!(worst <= kRebase))) {
+#pragma unroll
+          for (int s = 0; s < NQ; s++) st[s] = before[s];
+#pragma unroll
+          for (int u = 0; u < 2 * NQ - 1; u++) {
+            if (u == 0 || u == NQ) read_frags<HD>(kf, cur, u / NQ, l32, hi);
+            mfma_chain<KS>(accA, kf, qf[u % NQ]);
+            stats_fold(accA, st[u % NQ], c2);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 2 * NQ; u++) {
+          const int s = u % NQ, sp = (u + NQ * 2 - 1) % NQ;
+          if (u == NQ) read_frags<HD>(kf, cur, 1, l32, hi);
+          if (u & 1) stats_unit<KS>(accB, kf, qf[s], accA, st[sp], c2);
+          else       stats_unit<KS>(accA, kf, qf[s], accB, st[sp], c2);
+        }
       }
     }
     wait_vmem();
