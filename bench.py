@@ -35,6 +35,9 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_FP32_VALU_TFLOPS = 157.3    # MI355X fp32 vector (the fp32 workload runs plain FMAs)
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+# What the chip sustains, chip-wide, for v_mfma_f32_32x32x16_bf16 with Eq. 1's softmax arithmetic (two multiply-add /
+# exp2 / add triples) behind each, all operands in registers: profiles/microbench_mfma_softmax_ceiling.txt
+SUSTAINED_MFMA_SOFTMAX_TFLOPS = 1417.0
 DISTINCT_SETS_BUDGET = 100e9     # bytes of K+V that may be spent on one set per step
 
 
@@ -385,7 +388,13 @@ def main():
         a = m["score_tflops_algorithmic"]
         roofline = {"kernel": "score (score_stats + score_reduce)", "bound": "mfma", "achieved": a,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": a / PEAK_BF16_MFMA_TFLOPS,
-                    "traffic": score_traffic, "traffic_source": score_src}
+                    "traffic": score_traffic, "traffic_source": score_src,
+                    "executed": {"tflops": 2 * a, "frac_of_peak": 2 * a / PEAK_BF16_MFMA_TFLOPS,
+                                 "sustained_tflops_for_this_instruction_mix": SUSTAINED_MFMA_SOFTMAX_TFLOPS,
+                                 "frac_of_sustained": 2 * a / SUSTAINED_MFMA_SOFTMAX_TFLOPS,
+                                 "note": "the step evaluates Q.K^T twice (row normalisers, then column reduction); "
+                                         "the sustained figure is a microbenchmark of the same MFMA + softmax "
+                                         "instruction mix with nothing else going on"}}
     else:
         traffic, src = profiled_traffic(w.name, "compact")
         roofline = {"kernel": "compact_rows", "bound": "hbm", "achieved": m["compact_gbs"], "peak": PEAK_HBM_GBS,
