@@ -556,6 +556,14 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
     for (int j = 0; j < KS; j++)
       kf[s][j] = as_frag(*reinterpret_cast<const uint4*>(krow + j * 16));
   }
+  // The fragments are used here, i.e. loaded before the wait below.  Left to itself the compiler sinks these
+  // loads behind the barrier, finds them outstanding at the loop's entry and puts a counted wait in front of the
+  // first use of each inside the loop; from the second iteration on those waits only see the tile in flight and
+  // make every wave wait for it a unit and a half after it was requested.
+#pragma unroll
+  for (int s = 0; s < 2; s++)
+#pragma unroll
+    for (int j = 0; j < KS; j++) asm volatile("" : "+v"(kf[s][j]));
 
   // SUM: running sum of weights.  MAX: running max of the base-2 log weight
   // (exp2 is monotone, so one exponential per key at the end is enough).
