@@ -2,7 +2,10 @@
 """Eviction-step throughput on one MI355X.
 
 One step = one pass of the whole hot path (score -> top-M -> in-place compaction,
-one epicache_evict_step call) over one batch of synthetic input: all L layers x
+one epicache_evict_step_overlapped call: the step with the compaction of one part
+of the batch on a second stream beside the scoring of the next, where the library
+finds that worthwhile, else the plain epicache_evict_step) over one batch of
+synthetic input: all L layers x
 E episodes of a workload folded into the batch axis.  The default workload is the
 largest one, "stress": 32 layers x 16 episodes = 512 caches of 8 KV heads,
 M = 16384 cached + 8192 block rows per head, 256 patch queries per query head,
@@ -142,18 +145,26 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
         k0, v0 = torch.empty_like(kmaster), torch.empty_like(vmaster)
     prm = ep.make_params(q0, k0, n_cached=w.M, n_block=w.B, budget=w.M, reduce=reduce)
     ws = ep.alloc_workspace(prm)
+    # The timed step is epicache_evict_step_overlapped with the library's own choice of chunks: scoring and selection
+    # of chunk c + 1 on the launch stream beside the compaction of chunk c on a second stream (one chunk, i.e. the
+    # plain epicache_evict_step, where that does not pay).
+    ws_bytes, n_chunks = ep.epicache_overlapped_workspace_size(prm, 0)
+    ws_step = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    aux = torch.cuda.Stream()
+
+    def step(q, k, v):
+        ep.epicache_evict_step_overlapped(prm, q, k, v, ws_step, aux, 0)
+
     torch.cuda.synchronize()
 
     # ---- whole-step timing: W warm-up steps, then exactly K timed steps
     if distinct:
         for s in range(warmup):
-            q, k, v = sets[s]
-            ep.epicache_evict_step(prm, q, k, v, ws)
+            step(*sets[s])
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(warmup, n_sets):
-            q, k, v = sets[s]
-            ep.epicache_evict_step(prm, q, k, v, ws)
+            step(*sets[s])
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         timing = "K steps back to back in one bracket, each on its own input set"
@@ -165,7 +176,7 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
             k0.copy_(kmaster), v0.copy_(vmaster)     # restore, outside the timed interval
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            ep.epicache_evict_step(prm, q0, k0, v0, ws)
+            step(q0, k0, v0)
             torch.cuda.synchronize()
             if s >= warmup:
                 elapsed += time.perf_counter() - t0
@@ -173,9 +184,20 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
         kfresh, vfresh = kmaster, vmaster
     ms_per_step = elapsed / steps * 1e3
 
-    # ---- per-stage timing with HIP events on the launch stream (same launch configuration:
-    # epicache_evict_step enqueues exactly these three calls)
+    # ---- the same step with the stages one after the other on one stream (epicache_evict_step)
     kp, vp = k0, v0
+    ev = events(stage_reps + 1, 2)
+    for e in ev:
+        kp.copy_(kfresh), vp.copy_(vfresh)
+        e[0].record()
+        ep.epicache_evict_step(prm, q0, kp, vp, ws)
+        e[1].record()
+    torch.cuda.synchronize()
+    t_step_serial = mean_ms(ev[1:], 0) * 1e-3
+
+    # ---- per-stage timing with HIP events on the launch stream (whole batch per launch, the launch configuration
+    # of epicache_evict_step, which enqueues exactly these three calls; the overlapped step launches the same
+    # kernels once per chunk)
     scores = torch.empty(nb, w.Hkv, w.N, dtype=torch.float32, device=dev)
     keep = torch.empty(nb, w.Hkv, w.M, dtype=torch.int32, device=dev)
     ev = events(stage_reps + 1, 4)
@@ -234,6 +256,10 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
                     f"Hq/Hkv={w.Hq}/{w.Hkv}, d={w.d}, {w.dtype}, M={w.M}, block={w.B}, patch={w.p}, reduce={reduce_name}",
         "tokens_per_step": tokens_per_step, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_step / (elapsed / steps),
         "timing": timing, "bytes_per_input_set": bytes_per_set,
+        "step_entry_point": f"epicache_evict_step_overlapped, {n_chunks} chunk(s)" +
+                            (": the plain step" if n_chunks == 1 else
+                             ", compaction of a chunk on a second stream beside the scoring of the next"),
+        "serial_step_ms": t_step_serial * 1e3,
         "score_ms": t_score * 1e3, "topk_ms": t_topk * 1e3, "compact_ms": t_compact * 1e3,
         "score_tflops_algorithmic": flops_score / t_score / 1e12,
         "score_frac_peak_algorithmic": flops_score / t_score / 1e12 / peak_score,
@@ -405,14 +431,17 @@ def main():
         "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": m["workload"], "tokens_per_step": m["tokens_per_step"], "timing": m["timing"]},
+        "config": {"workload": m["workload"], "tokens_per_step": m["tokens_per_step"], "timing": m["timing"],
+                   "step_entry_point": m["step_entry_point"]},
+        "serial_step_ms": m["serial_step_ms"],
         "roofline": roofline,
         "stages": stages,
     }
 
     if not args.no_other_configs:
         # the same figures for the other workloads, each with all its layers folded into one launch
-        configs = {w.name: {k: m[k] for k in ("ms_per_step", "tokens_per_s", "score_ms", "score_frac_peak_algorithmic",
+        configs = {w.name: {k: m[k] for k in ("ms_per_step", "serial_step_ms", "step_entry_point", "tokens_per_s", "score_ms",
+                                              "score_frac_peak_algorithmic",
                                               "score_frac_peak_executed", "score_peak_kind", "compact_ms",
                                               "select_plus_compact_frac_hbm_peak")}}
         for name, ow in synth.WORKLOADS.items():
@@ -421,7 +450,8 @@ def main():
             steps = 20 if ow.L * ow.E * ow.Hkv * ow.N * ow.d < 6e9 else 10
             om = measure(ow, args.reduce, steps, 2, args.stage_reps, extras=False)
             free_gpu()
-            configs[name] = {k: om[k] for k in ("ms_per_step", "tokens_per_s", "score_ms", "score_frac_peak_algorithmic",
+            configs[name] = {k: om[k] for k in ("ms_per_step", "serial_step_ms", "step_entry_point", "tokens_per_s", "score_ms",
+                                                "score_frac_peak_algorithmic",
                                                 "score_frac_peak_executed", "score_peak_kind", "compact_ms",
                                                 "select_plus_compact_frac_hbm_peak")}
             configs[name]["workload"] = om["workload"]

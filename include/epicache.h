@@ -10,13 +10,13 @@
  * batch axis, all layers) are processed by one call.
  *
  * Conventions that hold for every entry point
- *   - `params`, `bytes_out`, `keep_capacity_out` and the arrays of
- *     epicache_layer_budgets are HOST pointers.  Every other pointer is a
+ *   - `params`, `bytes_out`, `keep_capacity_out`, `n_chunks_out` and the arrays
+ *     of epicache_layer_budgets are HOST pointers.  Every other pointer is a
  *     DEVICE pointer, 16-byte aligned, owned by the caller.  The library never
  *     allocates, frees or retains device memory and keeps no state between
- *     calls (epicache_evict_step_static documents the one exception), so it may
- *     be called from several host threads and its calls may be captured into a
- *     HIP graph.
+ *     calls (epicache_evict_step_static and epicache_evict_step_overlapped
+ *     document the two exceptions), so it may be called from several host
+ *     threads and its calls may be captured into a HIP graph.
  *   - A call validates its arguments on the host, enqueues its kernels on
  *     `hip_stream` (a hipStream_t; NULL = the default stream) and returns
  *     without synchronising.  The return value is an epicache_status; it
@@ -157,6 +157,31 @@ EPICACHE_API int epicache_evict_step(const epicache_params* params, const void* 
 #define EPICACHE_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
 EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const void* q, void* k, void* v,
                         float* scores_opt, int32_t* keep_idx_opt, void* hip_stream);
+
+/* Alg. 1 phase A3, one block, as a two-stream pipeline.  The batch is cut into chunks of whole batch items
+ * (every (batch item, KV head) of the step is independent, Sec. 3.1 Stage 2); scoring and selection of chunk
+ * c + 1 run on `hip_stream` while the in-place compaction of chunk c runs on `hip_stream_aux`, so the
+ * memory-bound copy proceeds beside the arithmetic-bound scoring instead of after it.  Results as
+ * epicache_evict_step, except that the scores may differ from that call's in the last bits (the key splits of
+ * the first scoring pass follow the size of the launch, and with them the order of a row's sum).
+ *   n_chunks         0 = chosen by the library (1, i.e. the plain step, where overlapping does not pay:
+ *                    fewer than 256 scoring rows, no MFMA path, or nothing to evict); otherwise 1..32, and
+ *                    never more than n_batch.  epicache_overlapped_workspace_size reports the number used.
+ *   workspace        at least the size epicache_overlapped_workspace_size reports for the same params and
+ *                    n_chunks (every chunk has its own slice; scores_opt / keep_idx_opt do not shrink it).
+ *   hip_stream_aux   a second stream of the same device, default priority.  Equal to hip_stream: the chunks
+ *                    run one after the other on that stream.
+ * Ordering seen by the caller: everything is ordered after the work already enqueued on `hip_stream`, and
+ * `hip_stream` waits for the last compaction before the call's successors run, so the call behaves like a
+ * single-stream call; `hip_stream_aux` must carry no other work that touches K, V or the workspace.
+ * State: the events that order the two streams come from a pool the library creates on the first such call
+ * on a device and keeps until the process ends (host-side objects; no device memory).  The device current at
+ * the call must be the one both streams belong to.  Not for HIP graph capture. */
+EPICACHE_API int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks,
+                        size_t* bytes_out, int32_t* n_chunks_out);
+EPICACHE_API int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,
+                        float* scores_opt, int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
+                        size_t workspace_bytes, void* hip_stream, void* hip_stream_aux);
 
 /* epicache_evict_step with the scoring done by epicache_score_lse: for callers whose prefill
  * attention kernel already returned each patch row's log-sum-exp (row_lse as documented there).

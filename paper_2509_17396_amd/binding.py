@@ -24,6 +24,7 @@ SELECT_PER_HEAD, SELECT_POOLED = 0, 1
 ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_evict_step_static", "epicache_evict_step_lse", "epicache_layer_budgets",
+    "epicache_overlapped_workspace_size", "epicache_evict_step_overlapped",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
     "epicache_evict_step_ragged", "epicache_snapkv_workspace_size", "epicache_evict_step_snapkv",
     "epicache_kvzip_workspace_size", "epicache_score_kvzip", "epicache_evict_step_kvzip", "epicache_score_keydiff", "epicache_patch_attention",
@@ -93,6 +94,9 @@ def load() -> ctypes.CDLL:
     lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.epicache_evict_step_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_overlapped_workspace_size.argtypes = [pp, ctypes.c_int32, ctypes.POINTER(sz),
+                                                       ctypes.POINTER(ctypes.c_int32)]
+    lib.epicache_evict_step_overlapped.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp, vp]
     lib.epicache_layer_budgets.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     i32c = ctypes.c_int32
@@ -199,6 +203,23 @@ STATIC_SCRATCH_BYTES = 64 << 20
 def epicache_evict_step_static(params: Params, q, k, v, scores=None, keep_idx=None) -> None:
     _check(load().epicache_evict_step_static(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
                                              _ptr(keep_idx), _stream()), "epicache_evict_step_static")
+
+
+def epicache_overlapped_workspace_size(params: Params, n_chunks: int = 0):
+    """(bytes, number of chunks the step will use)"""
+    out, used = ctypes.c_size_t(0), ctypes.c_int32(0)
+    _check(load().epicache_overlapped_workspace_size(ctypes.byref(params), n_chunks, ctypes.byref(out),
+                                                     ctypes.byref(used)), "epicache_overlapped_workspace_size")
+    return out.value, used.value
+
+
+def epicache_evict_step_overlapped(params: Params, q, k, v, workspace, aux_stream, n_chunks: int = 0, scores=None,
+                                   keep_idx=None) -> None:
+    """aux_stream: a torch.cuda.Stream of the same device (the compactions run there)."""
+    _check(load().epicache_evict_step_overlapped(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
+                                                 _ptr(keep_idx), n_chunks, _ptr(workspace), workspace.numel(),
+                                                 _stream(), ctypes.c_void_p(aux_stream.cuda_stream)),
+           "epicache_evict_step_overlapped")
 
 
 def epicache_evict_step_lse(params: Params, q, k, v, row_lse, workspace, scores=None, keep_idx=None) -> None:

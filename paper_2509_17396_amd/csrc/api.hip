@@ -325,6 +325,86 @@ static void* static_scratch() {
   return scratch_ptr[dev];
 }
 
+// ---- the step as a two-stream pipeline over chunks of the batch (epicache_evict_step_overlapped)
+constexpr int kMaxOverlapChunks = 32;
+
+struct OverlapPlan {
+  Plan whole;            // the step as one launch: validation, N, M
+  Plan body, tail;       // a chunk of chunk_nb batch items; the last chunk (tail_nb items, 1..chunk_nb)
+  int n_chunks, chunk_nb, tail_nb;
+  size_t total;          // bytes: every chunk has its own workspace slice
+};
+
+static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, OverlapPlan* out) {
+  OverlapPlan op;
+  int st = make_plan(prm, &op.whole);
+  if (st != EPICACHE_OK) return st;
+  if (n_chunks < 0 || n_chunks > kMaxOverlapChunks) return EPICACHE_ERR_INVALID_ARG;
+  const Plan& pw = op.whole;
+  int n = n_chunks;
+  if (n == 0) {
+    // Overlap pays where the scoring is bound by arithmetic and leaves HBM idle: the MFMA path with at least
+    // 256 scoring rows per KV head.  Chunks of some 128 (batch item, head) pairs keep every launch at a round
+    // of resident workgroups or more.
+    const int64_t nbh = (int64_t)pw.nb * pw.Hkv;
+    n = (pw.use_mfma && pw.R >= 256 && pw.N > pw.M) ? (int)(nbh / 128) : 1;
+    if (n < 1) n = 1;
+    if (n > kMaxOverlapChunks) n = kMaxOverlapChunks;
+  }
+  if (n > pw.nb) n = pw.nb;
+  op.chunk_nb = (pw.nb + n - 1) / n;
+  op.n_chunks = (pw.nb + op.chunk_nb - 1) / op.chunk_nb;
+  op.tail_nb = pw.nb - (op.n_chunks - 1) * op.chunk_nb;
+  epicache_params pc = *prm;
+  pc.n_batch = op.chunk_nb;
+  st = make_plan(&pc, &op.body);
+  if (st != EPICACHE_OK) return st;
+  op.tail = op.body;
+  if (op.tail_nb != op.chunk_nb) {
+    pc.n_batch = op.tail_nb;
+    st = make_plan(&pc, &op.tail);
+    if (st != EPICACHE_OK) return st;
+  }
+  op.total = (size_t)(op.n_chunks - 1) * op.body.ws_total + op.tail.ws_total;
+  *out = op;
+  return EPICACHE_OK;
+}
+
+// Events that order the two streams of epicache_evict_step_overlapped: one per chunk (selection done ->
+// compaction may start) and one for the join.  Created once per device, kept until the process ends.  A wait
+// refers to the record that precedes it at the time it is enqueued, so the pool can be reused by the next call
+// while the previous one is still running; the mutex is held from a call's first record to its last wait, so
+// two host threads never interleave their records and waits.
+struct OverlapEvents {
+  hipEvent_t chunk[kMaxOverlapChunks];
+  hipEvent_t join;
+  bool ready;
+};
+static std::mutex overlap_mutex;
+static OverlapEvents overlap_events[kMaxDevices];
+
+// call with overlap_mutex held; null if the device is out of range or an event cannot be created
+static OverlapEvents* overlap_event_pool() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  OverlapEvents& ev = overlap_events[dev];
+  if (!ev.ready) {
+    hipEvent_t made[kMaxOverlapChunks + 1];
+    int n = 0;
+    for (; n <= kMaxOverlapChunks; n++)
+      if (hipEventCreateWithFlags(&made[n], hipEventDisableTiming) != hipSuccess) break;
+    if (n <= kMaxOverlapChunks) {
+      (void)hipGetLastError();
+      for (int i = 0; i < n; i++) (void)hipEventDestroy(made[i]);
+      return nullptr;
+    }
+    for (int i = 0; i < kMaxOverlapChunks; i++) ev.chunk[i] = made[i];
+    ev.join = made[kMaxOverlapChunks];
+    ev.ready = true;
+  }
+  return &ev;
+}
+
 }  // namespace epicache
 
 using namespace epicache;
@@ -534,6 +614,81 @@ int epicache_evict_step_static(const epicache_params* params, const void* q, voi
   if (!ws) return EPICACHE_ERR_DEVICE;
   return evict_step_impl(params, q, k, v, nullptr, false, scores_opt, keep_idx_opt, ws,
                          kStaticScratchBytes, hip_stream);
+}
+
+int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks, size_t* bytes_out,
+                                       int32_t* n_chunks_out) {
+  if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
+  OverlapPlan op;
+  int st = make_overlap_plan(params, n_chunks, &op);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = op.total;
+  if (n_chunks_out) *n_chunks_out = op.n_chunks;
+  return EPICACHE_OK;
+}
+
+int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,
+                                   float* scores_opt, int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream, void* hip_stream_aux) {
+  OverlapPlan op;
+  int st = make_overlap_plan(params, n_chunks, &op);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) || misaligned(scores_opt) ||
+      misaligned(keep_idx_opt))
+    return EPICACHE_ERR_INVALID_ARG;
+  if (k == v) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < op.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  const Plan& pw = op.whole;
+  hipStream_t main_stream = (hipStream_t)hip_stream, aux_stream = (hipStream_t)hip_stream_aux;
+  const bool two_streams = main_stream != aux_stream && op.n_chunks > 1 && pw.N > pw.M;
+
+  std::unique_lock<std::mutex> lock(overlap_mutex, std::defer_lock);
+  OverlapEvents* ev = nullptr;
+  if (two_streams) {
+    lock.lock();
+    ev = overlap_event_pool();
+    if (!ev) return EPICACHE_ERR_DEVICE;
+  }
+  char* ws = static_cast<char*>(workspace);
+  int result = EPICACHE_OK;
+  bool forked = false;
+  for (int c = 0; c < op.n_chunks && result == EPICACHE_OK; c++) {
+    const Plan& pc = c + 1 < op.n_chunks ? op.body : op.tail;
+    const int64_t b0 = (int64_t)c * op.chunk_nb;  // first batch item of the chunk
+    const char* qc = static_cast<const char*>(q) + b0 * pw.qsb * pw.elem;
+    char* kc = static_cast<char*>(k) + b0 * pw.ksb * pw.elem;
+    char* vc = static_cast<char*>(v) + b0 * pw.ksb * pw.elem;
+    char* wc = ws + (size_t)c * op.body.ws_total;
+    float* scores = scores_opt ? scores_opt + b0 * pw.Hkv * pw.N : reinterpret_cast<float*>(wc + pc.off_scores);
+    int32_t* keep = keep_idx_opt ? keep_idx_opt + b0 * pw.Hkv * pw.n_keep
+                                 : reinterpret_cast<int32_t*>(wc + pc.off_keep);
+    if (pw.N <= pw.M) {  // nothing to evict: as epicache_evict_step
+      if (scores_opt) result = run_score(pc, qc, kc, scores, wc, main_stream);
+      if (result == EPICACHE_OK && keep_idx_opt && launch_iota_keep(pc, keep, main_stream) != hipSuccess)
+        result = EPICACHE_ERR_DEVICE;
+      continue;
+    }
+    result = run_score(pc, qc, kc, scores, wc, main_stream);
+    if (result != EPICACHE_OK) break;
+    if (launch_topk(pc, scores, keep, main_stream) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
+    hipStream_t copy_stream = main_stream;
+    if (two_streams) {
+      // the compaction of this chunk waits for its selection only; the next chunk's scoring does not wait for it
+      if (hipEventRecord(ev->chunk[c], main_stream) != hipSuccess ||
+          hipStreamWaitEvent(aux_stream, ev->chunk[c], 0) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
+      forked = true;
+      copy_stream = aux_stream;
+    }
+    if (launch_compact(pc, keep, kc, vc, copy_stream) != hipSuccess) result = EPICACHE_ERR_DEVICE;
+  }
+  if (forked) {
+    // join, also after a failed launch: whatever follows on hip_stream is ordered after the compactions enqueued so far
+    if (hipEventRecord(ev->join, aux_stream) != hipSuccess ||
+        hipStreamWaitEvent(main_stream, ev->join, 0) != hipSuccess)
+      result = EPICACHE_ERR_DEVICE;
+  }
+  return result;
 }
 
 int epicache_evict_step_lse(const epicache_params* params, const void* q, void* k, void* v,

@@ -115,3 +115,39 @@ def test_snapkv_and_kvzip_plans_never_crash_and_follow_their_rules(g):
     else:
         assert st_k == ep.OK, (g, st_k)
         assert size.value % 256 == 0 and size.value >= 2 * nb * Hkv * N * 4 + nb * Hkv * min(budget, N) * 4
+
+
+@settings(max_examples=300, deadline=None)
+@given(geometry, st.integers(-2, 40))
+def test_overlapped_plans_cover_the_batch_and_their_chunks(g, asked):
+    nb, Hkv, G, p, d, n_cached, n_block, budget, dtype, reduce, causal, extra, pad = g
+    prm = _dense_params(*g)
+    lib = ep.load()
+    size, plain, used = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int32(-1)
+    st_plain = lib.epicache_workspace_size(ctypes.byref(prm), ctypes.byref(plain))
+    st_o = lib.epicache_overlapped_workspace_size(ctypes.byref(prm), asked, ctypes.byref(size), ctypes.byref(used))
+    if st_plain != ep.OK:
+        assert st_o == st_plain
+        return
+    if asked < 0 or asked > 32:
+        assert st_o == ep.ERR_INVALID_ARG
+        return
+    assert st_o == ep.OK, (g, asked, st_o)
+    n = used.value
+    assert 1 <= n <= min(32, nb)
+    if asked:
+        # chunks of ceil(nb / asked) batch items each, the last one shorter
+        per = -(-nb // min(asked, nb))
+        assert n == -(-nb // per)
+    per = -(-nb // n)
+    # every chunk's slice is the workspace of a step over that chunk
+    one = _dense_params(per, *g[1:])
+    body = ctypes.c_size_t(0)
+    assert lib.epicache_workspace_size(ctypes.byref(one), ctypes.byref(body)) == ep.OK
+    tail_nb = nb - (n - 1) * per
+    assert 1 <= tail_nb <= per
+    tail = ctypes.c_size_t(0)
+    assert lib.epicache_workspace_size(ctypes.byref(_dense_params(tail_nb, *g[1:])), ctypes.byref(tail)) == ep.OK
+    assert size.value == (n - 1) * body.value + tail.value
+    if n == 1:
+        assert size.value == plain.value
