@@ -26,12 +26,20 @@ def say(msg):
     sys.stdout.flush()
 
 
-def evict_on_gpu(q, k, v, M, N, reduce):
+def evict_on_gpu(q, k, v, M, N, reduce, overlapped=False):
+    """overlapped: through epicache_evict_step_overlapped with the library's own choice of chunks (the call
+    bench.py times); returns the number of batch items per chunk as a third value then."""
     prm = ep.make_params(q, k, n_cached=min(M, N), n_block=N - min(M, N), budget=M, reduce=reduce)
-    ws = ep.alloc_workspace(prm)
     nb, H = q.shape[0], k.shape[1]
     scores = torch.full((nb, H, N), float("nan"), dtype=torch.float32, device=DEV)
     keep = torch.full((nb, H, min(M, N)), -1, dtype=torch.int32, device=DEV)
+    if overlapped:
+        nbytes, chunks = ep.epicache_overlapped_workspace_size(prm, 0)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        ep.epicache_evict_step_overlapped(prm, q, k, v, ws, torch.cuda.Stream(), 0, scores, keep)
+        torch.cuda.synchronize()
+        return scores, keep, -(-nb // chunks)
+    ws = ep.alloc_workspace(prm)
     ep.epicache_evict_step(prm, q, k, v, ws, scores, keep)
     torch.cuda.synchronize()
     return scores, keep
@@ -124,17 +132,26 @@ FOLDED_CASES = [
 ]
 
 
+@pytest.mark.parametrize("entry", ["one_launch", "overlapped"])
 @pytest.mark.parametrize("name,samples", FOLDED_CASES, ids=[c[0] for c in FOLDED_CASES])
-def test_configs_3_to_5_all_layers_folded_as_benchmarked(name, samples):
-    """The launch bench.py times for the large workloads: all L layers x E episodes in one call
-    (stress: 512 caches x 8 KV heads of 24576 rows).  Properties over the whole batch on the device,
-    eight sampled heads against the oracle."""
+def test_configs_3_to_5_all_layers_folded_as_benchmarked(name, samples, entry):
+    """The calls bench.py times for the large workloads: all L layers x E episodes in one call
+    (stress: 512 caches x 8 KV heads of 24576 rows), as one launch per stage (epicache_evict_step) and as the
+    two-stream pipeline over chunks that the headline is quoted on (epicache_evict_step_overlapped, chunks chosen by
+    the library).  Properties over the whole batch on the device, eight sampled heads against the oracle, plus the
+    last head of one chunk and the first of the next for the pipeline."""
     w = synth.WORKLOADS[name]
     reduce = orc.REDUCE_SUM
-    say(f"{name} folded L={w.L} x E={w.E} = {w.L * w.E} caches")
+    say(f"{name} folded L={w.L} x E={w.E} = {w.L * w.E} caches, {entry}")
     q, k0, v0 = synth.make_folded(w, range(w.L), device=DEV)
     k, v = k0.clone(), v0.clone()
-    scores, keep = evict_on_gpu(q, k, v, w.M, w.N, reduce)
+    if entry == "overlapped":
+        scores, keep, per_chunk = evict_on_gpu(q, k, v, w.M, w.N, reduce, overlapped=True)
+        assert per_chunk < w.L * w.E, "the library runs these workloads in more than one chunk"
+        say(f"  {per_chunk} caches per chunk")
+        samples = samples + [(per_chunk - 1, w.Hkv - 1), (per_chunk, 0)]
+    else:
+        scores, keep = evict_on_gpu(q, k, v, w.M, w.N, reduce)
     check_sampled(q, k0, v0, k, v, scores, keep, w.M, w.N, reduce, [], name)
     del k, v, v0
     differ, worst = check_heads_against_oracle(q, k0, scores, keep, w.M, w.N, reduce, samples, name)
