@@ -523,10 +523,20 @@ __global__ __launch_bounds__(256, 2) void score_reduce(const bf16_t* __restrict_
   uint32_t qoff[ST::kPer];
   ST::offsets(qoff, wave, lane, qstride);
   const uint32_t lds0 = lds_address(lds);
+  // dense tiles are staged in order, so the address of the next one is carried along instead of being derived
+  // from the tile index with a division per tile
+  const unsigned char* qtile = qbase;  // first row of the next tile to stage
+  int qtile_row = 0;                   // that row's index within its query head
   auto stage_queries = [&](uint32_t dst, int t) {
     if (dense_tiles) {
-      const int r0 = t * 64;
-      ST::run(dst, qbase + (size_t)(r0 / p) * qsh + (size_t)(r0 % p) * qstride, qoff, wave);
+      ST::run(dst, qtile, qoff, wave);
+      qtile_row += 64;
+      if (qtile_row == p) {
+        qtile_row = 0;
+        qtile += qsh - (size_t)(p - 64) * qstride;  // first row of the next query head
+      } else {
+        qtile += (size_t)64 * qstride;
+      }
     } else {
       // rows beyond R re-read the last row; their -lse is -inf, so they contribute nothing
       ST::run_rows(dst, wave, lane, [=](int row) {
