@@ -37,7 +37,8 @@ __global__ __launch_bounds__(1024) void ragged_threshold(const float* __restrict
                                                          HeadRecord* __restrict__ rec,
                                                          int32_t* __restrict__ n_kept, Plan pl) {
   constexpr int kSeg = POOLED ? kMaxPooledHeads : 1;
-  __shared__ uint32_t hist[4][256];
+  __shared__ uint32_t hist_rep[256 * kHistCopies];  // one digit's histogram, every bin once per LDS bank
+  __shared__ uint32_t hist[256];
   __shared__ int seg_len[kSeg];
   __shared__ uint32_t seg_gt[kSeg], seg_eq[kSeg];
   __shared__ unsigned long long pool_total;
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(1024) void ragged_threshold(const float* __restrict
   const int M = item_budget(pl, budgets, b);
 
   if (tid == 0) pool_total = 0;
-  for (int i = tid; i < 4 * 256; i += blockDim.x) (&hist[0][0])[i] = 0;
+  for (int i = tid; i < 256 * kHistCopies; i += blockDim.x) hist_rep[i] = 0;
   __syncthreads();
   for (int s = tid; s < nh; s += blockDim.x) {
     const int n = ctx_rows(pl, bh_first + s);
@@ -80,12 +81,14 @@ __global__ __launch_bounds__(1024) void ragged_threshold(const float* __restrict
       const int n = seg_len[s];
       for (int i = tid; i < n; i += blockDim.x) {
         const uint32_t key = order_key(row[i]);
-        if ((key & mask) == prefix) atomicAdd(&hist[pass][(key >> shift) & 255u], 1u);
+        if ((key & mask) == prefix) hist_count(hist_rep, (key >> shift) & 255u, lane);
       }
     }
     __syncthreads();
+    hist_fold(hist_rep, hist, tid);
+    __syncthreads();
     uint32_t bin, above;
-    locate_digit(hist[pass], kth, lane, bin, above);
+    locate_digit(hist, kth, lane, bin, above);
     prefix |= bin << shift;
     mask |= 255u << shift;
     kth -= above;

@@ -17,6 +17,32 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// Histogram of one radix digit in LDS.  The scores of a row share few values of the leading digits (sign and
+// exponent), so with a plain 256-bin array most of a wave's 64 atomics would meet on one address, which LDS
+// serialises.  Every bin is therefore kept in kHistCopies copies, one per LDS bank (copy = lane % 32): at most two
+// lanes of an instruction meet on an address.  hist_rep holds 256 * kHistCopies counters, all zero before a pass.
+constexpr int kHistCopies = 32;
+
+__device__ __forceinline__ void hist_count(uint32_t* hist_rep, uint32_t digit, int lane) {
+  atomicAdd(&hist_rep[digit * kHistCopies + (lane & (kHistCopies - 1))], 1u);
+}
+
+// Between two workgroup barriers, by every thread of a workgroup of at least 256: thread t < 256 folds the copies
+// of bin t into hist[t] (reading them in a rotated order, so the lanes of a wave stay on different banks) and
+// clears them for the next pass.
+__device__ __forceinline__ void hist_fold(uint32_t* hist_rep, uint32_t* hist, int tid) {
+  if (tid < 256) {
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (int c = 0; c < kHistCopies; c++) {
+      uint32_t& slot = hist_rep[tid * kHistCopies + ((c + tid) & (kHistCopies - 1))];
+      sum += slot;
+      slot = 0;
+    }
+    hist[tid] = sum;
+  }
+}
+
 // One radix digit of a select: given the 256-bin histogram of the digit among the keys that still
 // match the prefix, find the bin that holds the kth largest (kth >= 1 counts from the top) and how
 // many keys lie in the bins above it.  Every wave calls this with the same arguments and gets the

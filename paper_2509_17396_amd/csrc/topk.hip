@@ -14,18 +14,13 @@
 namespace epicache {
 namespace {
 
-constexpr int kCopies = 32;  // copies of every histogram bin, one per LDS bank
-
 // VPT > 0: each thread keeps VPT keys in registers (N <= blockDim.x * VPT).
 // VPT == 0: keys are re-read from global memory in every pass (any N).
 template <int VPT>
 __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ scores,
                                                     int32_t* __restrict__ keep, int N, int n_keep,
                                                     int pitch) {
-  // Scores of one row share few values of the leading digits (sign and exponent), so a plain 256-bin histogram
-  // would take most of a wave's 64 atomics on one address, which LDS serialises.  Every bin is therefore kept in
-  // kCopies copies, one per LDS bank (copy = lane % 32): at most two lanes of an instruction meet on an address.
-  __shared__ uint32_t hist_rep[256 * kCopies];
+  __shared__ uint32_t hist_rep[256 * kHistCopies];  // one digit's histogram, every bin once per LDS bank
   __shared__ uint32_t hist[256];
   __shared__ uint32_t wave_gt[16], wave_eq[16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -33,7 +28,6 @@ __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ sc
   const float* row = scores + (size_t)blockIdx.x * N;
   int32_t* out = keep + (size_t)blockIdx.x * pitch;  // rows of kept indices are `pitch` apart
 
-  const int copy = lane & (kCopies - 1);
   const int groups = VPT > 0 ? VPT : (N + nwaves * 64 - 1) / (nwaves * 64);  // 64-wide groups per wave
   const int base = wave * groups * 64 + lane;
 
@@ -51,7 +45,7 @@ __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ sc
     return i < N ? order_key(row[i]) : 0u;
   };
 
-  for (int i = tid; i < 256 * kCopies; i += blockDim.x) hist_rep[i] = 0;
+  for (int i = tid; i < 256 * kHistCopies; i += blockDim.x) hist_rep[i] = 0;
   __syncthreads();
 
   uint32_t prefix = 0, mask = 0;
@@ -63,29 +57,16 @@ __global__ __launch_bounds__(1024) void topk_select(const float* __restrict__ sc
 #pragma unroll
       for (int j = 0; j < VPT; j++) {
         const uint32_t key = key_at(j);
-        if (base + j * 64 < N && (key & mask) == prefix)
-          atomicAdd(&hist_rep[((key >> shift) & 255u) * kCopies + copy], 1u);
+        if (base + j * 64 < N && (key & mask) == prefix) hist_count(hist_rep, (key >> shift) & 255u, lane);
       }
     } else {
       for (int j = 0; j < groups; j++) {
         const uint32_t key = key_at(j);
-        if (base + j * 64 < N && (key & mask) == prefix)
-          atomicAdd(&hist_rep[((key >> shift) & 255u) * kCopies + copy], 1u);
+        if (base + j * 64 < N && (key & mask) == prefix) hist_count(hist_rep, (key >> shift) & 255u, lane);
       }
     }
     __syncthreads();
-    // fold the copies of bin `tid` (read in a rotated order, so the lanes of a wave stay on different banks) and
-    // clear them for the next pass
-    if (tid < 256) {
-      uint32_t sum = 0;
-#pragma unroll 8
-      for (int c = 0; c < kCopies; c++) {
-        uint32_t& slot = hist_rep[tid * kCopies + ((c + tid) & (kCopies - 1))];
-        sum += slot;
-        slot = 0;
-      }
-      hist[tid] = sum;
-    }
+    hist_fold(hist_rep, hist, tid);
     __syncthreads();
     uint32_t bin, above;
     locate_digit(hist, kth, lane, bin, above);  // every wave scans the 256 bins itself
