@@ -345,9 +345,16 @@ static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, Overl
   if (n == 0) {
     // Overlap pays where the scoring is bound by arithmetic and leaves HBM idle: the MFMA path with at least
     // 256 scoring rows per KV head.  Chunks of some 128 (batch item, head) pairs keep every launch at a round
-    // of resident workgroups or more.
+    // of resident workgroups or more, and a chunk should score for a quarter of a millisecond or so (2.5e11
+    // flops in the two passes), or its four launches cost more than the overlap returns.
     const int64_t nbh = (int64_t)pw.nb * pw.Hkv;
-    n = (pw.use_mfma && pw.R >= 256 && pw.N > pw.M) ? (int)(nbh / 128) : 1;
+    n = 1;
+    if (pw.use_mfma && pw.R >= 256 && pw.N > pw.M) {
+      const double flops = 4.0 * pw.R * (double)pw.N * pw.d * (double)nbh;
+      const double by_work = flops / 2.5e11;
+      n = (int)(nbh / 128);
+      if ((double)n > by_work) n = (int)by_work;
+    }
     if (n < 1) n = 1;
     if (n > kMaxOverlapChunks) n = kMaxOverlapChunks;
   }

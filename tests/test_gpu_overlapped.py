@@ -42,7 +42,8 @@ CASES = [
     (5, 4, 4, 16, 64, 333, 111, torch.bfloat16, 32, 5),      # more chunks asked than items: one item each
     (4, 4, 2, 8, 32, 200, 64, torch.float32, 2, 2),          # fp32 path
     (3, 8, 2, 64, 128, 600, 256, torch.bfloat16, 1, 1),      # one chunk: the plain step
-    (64, 16, 4, 64, 128, 512, 256, torch.bfloat16, 0, 2),    # library's choice: 256 scoring rows, 256 heads -> 2
+    (64, 16, 4, 64, 128, 512, 256, torch.bfloat16, 0, 1),    # library's choice: 256 heads of 256 rows, but too little work to cut
+    (64, 16, 4, 64, 128, 512, 256, torch.bfloat16, 2, 2),    # the same in two chunks of 32 items
     (8, 6, 2, 64, 128, 512, 256, torch.bfloat16, 0, 1),      # library's choice: 192 scoring rows -> plain step
     (4, 8, 2, 64, 128, 256, 300, torch.bfloat16, 2, 2),      # N <= M: nothing evicted
 ]

@@ -151,3 +151,20 @@ def test_overlapped_plans_cover_the_batch_and_their_chunks(g, asked):
     assert size.value == (n - 1) * body.value + tail.value
     if n == 1:
         assert size.value == plain.value
+
+
+def test_overlapped_chunk_choice_for_the_benchmarked_workloads():
+    """The library's own chunk count (n_chunks = 0): chunks of about 128 (item, head) pairs that still score for a
+    quarter of a millisecond each, none where the scoring has fewer than 256 rows per head."""
+    from paper_2509_17396_amd import synth
+    want = {"tiny": 1, "llama32_3b": 1, "llama31_8b": 8, "qwen25_7b": 7, "stress": 32}
+    for name, chunks in want.items():
+        w = synth.WORKLOADS[name]
+        nb, cap = w.L * w.E, w.M + w.B
+        dtype = ep.DTYPE_F32 if w.dtype == "f32" else ep.DTYPE_BF16
+        prm = ep.Params(ctypes.sizeof(ep.Params), nb, w.Hq, w.Hkv, w.d, w.M, w.B, w.M, w.p, dtype, ep.REDUCE_SUM, 0.0,
+                        0, 0, w.Hq * w.p * w.d, w.p * w.d, w.d, w.Hkv * cap * w.d, cap * w.d, w.d)
+        size, used = ctypes.c_size_t(0), ctypes.c_int32(0)
+        assert ep.load().epicache_overlapped_workspace_size(ctypes.byref(prm), 0, ctypes.byref(size),
+                                                            ctypes.byref(used)) == ep.OK
+        assert used.value == chunks, (name, used.value)
