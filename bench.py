@@ -2,8 +2,8 @@
 """Eviction-step throughput on one MI355X.
 
 One step = one pass of the whole hot path (score -> top-M -> in-place compaction,
-one epicache_evict_step_overlapped call: the step with the compaction of one part
-of the batch on a second stream beside the scoring of the next, where the library
+one epicache_evict_step_overlapped call: the step with the selection and compaction
+of one part of the batch on a second stream beside the scoring of the next, where the library
 finds that worthwhile, else the plain epicache_evict_step) over one batch of
 synthetic input: all L layers x
 E episodes of a workload folded into the batch axis.  The default workload is the
@@ -145,9 +145,9 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
         k0, v0 = torch.empty_like(kmaster), torch.empty_like(vmaster)
     prm = ep.make_params(q0, k0, n_cached=w.M, n_block=w.B, budget=w.M, reduce=reduce)
     ws = ep.alloc_workspace(prm)
-    # The timed step is epicache_evict_step_overlapped with the library's own choice of chunks: scoring and selection
-    # of chunk c + 1 on the launch stream beside the compaction of chunk c on a second stream (one chunk, i.e. the
-    # plain epicache_evict_step, where that does not pay).
+    # The timed step is epicache_evict_step_overlapped with the library's own choice of chunks: scoring of chunk
+    # c + 1 on the launch stream beside the selection and compaction of chunk c on a second stream (one chunk, i.e.
+    # the plain epicache_evict_step, where that does not pay).
     ws_bytes, n_chunks = ep.epicache_overlapped_workspace_size(prm, 0)
     ws_step = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     aux = torch.cuda.Stream()
@@ -258,7 +258,7 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras):
         "timing": timing, "bytes_per_input_set": bytes_per_set,
         "step_entry_point": f"epicache_evict_step_overlapped, {n_chunks} chunk(s)" +
                             (": the plain step" if n_chunks == 1 else
-                             ", compaction of a chunk on a second stream beside the scoring of the next"),
+                             ", selection and compaction of a chunk on a second stream beside the scoring of the next"),
         "serial_step_ms": t_step_serial * 1e3,
         "score_ms": t_score * 1e3, "topk_ms": t_topk * 1e3, "compact_ms": t_compact * 1e3,
         "score_tflops_algorithmic": flops_score / t_score / 1e12,

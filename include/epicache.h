@@ -159,13 +159,13 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
                         float* scores_opt, int32_t* keep_idx_opt, void* hip_stream);
 
 /* Alg. 1 phase A3, one block, as a two-stream pipeline.  The batch is cut into chunks of whole batch items
- * (every (batch item, KV head) of the step is independent, Sec. 3.1 Stage 2); scoring and selection of chunk
- * c + 1 run on `hip_stream` while the in-place compaction of chunk c runs on `hip_stream_aux`, so the
+ * (every (batch item, KV head) of the step is independent, Sec. 3.1 Stage 2); the scoring of chunk c + 1 runs
+ * on `hip_stream` while the selection and the in-place compaction of chunk c run on `hip_stream_aux`, so the
  * memory-bound copy proceeds beside the arithmetic-bound scoring instead of after it.  Results as
  * epicache_evict_step, except that the scores may differ from that call's in the last bits (the key splits of
  * the first scoring pass follow the size of the launch, and with them the order of a row's sum).
  *   n_chunks         0 = chosen by the library (1, i.e. the plain step, where overlapping does not pay:
- *                    fewer than 256 scoring rows, no MFMA path, or nothing to evict); otherwise 1..32, and
+ *                    fewer than 256 scoring rows, no MFMA path, or nothing to evict); otherwise 1..64, and
  *                    never more than n_batch.  epicache_overlapped_workspace_size reports the number used.
  *   workspace        at least the size epicache_overlapped_workspace_size reports for the same params and
  *                    n_chunks (every chunk has its own slice; scores_opt / keep_idx_opt do not shrink it).
@@ -173,7 +173,8 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  *                    run one after the other on that stream.
  * Ordering seen by the caller: everything is ordered after the work already enqueued on `hip_stream`, and
  * `hip_stream` waits for the last compaction before the call's successors run, so the call behaves like a
- * single-stream call; `hip_stream_aux` must carry no other work that touches K, V or the workspace.
+ * single-stream call; `hip_stream_aux` must carry no other work that touches K, V, the workspace, scores_opt
+ * or keep_idx_opt.
  * State: the events that order the two streams come from a pool the library creates on the first such call
  * on a device and keeps until the process ends (host-side objects; no device memory).  The device current at
  * the call must be the one both streams belong to.  Not for HIP graph capture. */

@@ -326,7 +326,7 @@ static void* static_scratch() {
 }
 
 // ---- the step as a two-stream pipeline over chunks of the batch (epicache_evict_step_overlapped)
-constexpr int kMaxOverlapChunks = 32;
+constexpr int kMaxOverlapChunks = 64;
 
 struct OverlapPlan {
   Plan whole;            // the step as one launch: validation, N, M
@@ -344,15 +344,15 @@ static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, Overl
   int n = n_chunks;
   if (n == 0) {
     // Overlap pays where the scoring is bound by arithmetic and leaves HBM idle: the MFMA path with at least
-    // 256 scoring rows per KV head.  Chunks of some 128 (batch item, head) pairs keep every launch at a round
-    // of resident workgroups or more, and a chunk should score for a quarter of a millisecond or so (2.5e11
-    // flops in the two passes), or its four launches cost more than the overlap returns.
+    // 256 scoring rows per KV head.  Chunks of some 64 (batch item, head) pairs keep every scoring launch at half
+    // a round of resident workgroups or more, and a chunk should score for a tenth of a millisecond or so
+    // (1.25e11 flops in the two passes), or its launches cost more than the overlap returns.
     const int64_t nbh = (int64_t)pw.nb * pw.Hkv;
     n = 1;
     if (pw.use_mfma && pw.R >= 256 && pw.N > pw.M) {
       const double flops = 4.0 * pw.R * (double)pw.N * pw.d * (double)nbh;
-      const double by_work = flops / 2.5e11;
-      n = (int)(nbh / 128);
+      const double by_work = flops / 1.25e11;
+      n = (int)(nbh / 64);
       if ((double)n > by_work) n = (int)by_work;
     }
     if (n < 1) n = 1;
@@ -377,8 +377,8 @@ static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, Overl
   return EPICACHE_OK;
 }
 
-// Events that order the two streams of epicache_evict_step_overlapped: one per chunk (selection done ->
-// compaction may start) and one for the join.  Created once per device, kept until the process ends.  A wait
+// Events that order the two streams of epicache_evict_step_overlapped: one per chunk (scores done ->
+// selection and compaction may start) and one for the join.  Created once per device, kept until the process ends.  A wait
 // refers to the record that precedes it at the time it is enqueued, so the pool can be reused by the next call
 // while the previous one is still running; the mutex is held from a call's first record to its last wait, so
 // two host threads never interleave their records and waits.
@@ -678,19 +678,20 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
     }
     result = run_score(pc, qc, kc, scores, wc, main_stream);
     if (result != EPICACHE_OK) break;
-    if (launch_topk(pc, scores, keep, main_stream) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
-    hipStream_t copy_stream = main_stream;
+    hipStream_t rest_stream = main_stream;
     if (two_streams) {
-      // the compaction of this chunk waits for its selection only; the next chunk's scoring does not wait for it
+      // selection and compaction of this chunk wait for its scores only; the next chunk's scoring does not wait
+      // for them
       if (hipEventRecord(ev->chunk[c], main_stream) != hipSuccess ||
           hipStreamWaitEvent(aux_stream, ev->chunk[c], 0) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
       forked = true;
-      copy_stream = aux_stream;
+      rest_stream = aux_stream;
     }
-    if (launch_compact(pc, keep, kc, vc, copy_stream) != hipSuccess) result = EPICACHE_ERR_DEVICE;
+    if (launch_topk(pc, scores, keep, rest_stream) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
+    if (launch_compact(pc, keep, kc, vc, rest_stream) != hipSuccess) result = EPICACHE_ERR_DEVICE;
   }
   if (forked) {
-    // join, also after a failed launch: whatever follows on hip_stream is ordered after the compactions enqueued so far
+    // join, also after a failed launch: whatever follows on hip_stream is ordered after the work enqueued on the other stream so far
     if (hipEventRecord(ev->join, aux_stream) != hipSuccess ||
         hipStreamWaitEvent(main_stream, ev->join, 0) != hipSuccess)
       result = EPICACHE_ERR_DEVICE;

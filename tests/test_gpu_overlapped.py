@@ -1,5 +1,5 @@
-"""epicache_evict_step_overlapped: the step as a two-stream pipeline over chunks of the batch (scoring and
-selection of chunk c + 1 beside the compaction of chunk c).  Every chunking must give what the oracle gives:
+"""epicache_evict_step_overlapped: the step as a two-stream pipeline over chunks of the batch (scoring of chunk
+c + 1 beside the selection and compaction of chunk c).  Every chunking must give what the oracle gives:
 scores elementwise, kept sets by the band rule, K/V the bit-exact gather of the kept rows; and what follows the
 call on the caller's stream must see the finished caches."""
 import ctypes
@@ -145,7 +145,7 @@ def test_overlapped_validation():
     lib = ep.load()
     prm = ep.make_params(q, k, n_cached=256, n_block=256, budget=256, reduce=ep.REDUCE_SUM)
     out, used = ctypes.c_size_t(0), ctypes.c_int32(0)
-    for bad in (-1, 33):
+    for bad in (-1, 65):
         assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), bad, ctypes.byref(out),
                                                       ctypes.byref(used)) == ep.ERR_INVALID_ARG
     assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), 2, ctypes.byref(out), ctypes.byref(used)) == ep.OK
