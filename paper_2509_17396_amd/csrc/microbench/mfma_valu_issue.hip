@@ -1,7 +1,8 @@
 // Microbenchmark, not part of libepicache: how the matrix cores and the vector ALU of one SIMD share issue, and
 // what the clock does when the whole chip runs such code.  Hand-written instruction streams (inline assembly, all
 // operands in registers): MFMAs alone, (multiply-add, exp2, add) triples alone, the two interleaved with the
-// accumulators in VGPRs or AccVGPRs, the 16x16x32 form, and the MFMAs bunched in front of the triples.  Run with
+// accumulators in VGPRs or AccVGPRs, the 16x16x32 form, the MFMAs bunched in front of the triples, and the
+// interleaved stream with idle cycles (s_sleep) behind every iteration.  Run with
 // 32 workgroups (an eighth of the CUs, one wave per SIMD: nothing throttles), 256 (every CU, one wave per SIMD)
 // and 512 (two waves per SIMD).
 // Build and run:  hipcc --offload-arch=gfx950 -O3 -std=c++17 -w -Xclang -target-feature -Xclang -packed-fp32-ops
@@ -32,6 +33,12 @@ __global__ __launch_bounds__(256) void k(const uint4* in, float* out, unsigned l
                    "v_mfma_f32_32x32x16_bf16 %[c2v], %[a], %[b], %[c2v]\n\t" T2A "v_mfma_f32_32x32x16_bf16 %[c3], %[a], %[b], %[c3]\n\t" T2B
                    : [c0] "+v"(c0), [c1] "+v"(c1), [c2v] "+v"(c2v), [c3] "+v"(c3), [x0] "+v"(x0), [x1] "+v"(x1), [x2] "+v"(x2), [x3] "+v"(x3), [s0] "+v"(s0), [s1] "+v"(s1)
                    : [a] "v"(a), [b] "v"(b), [c2] "v"(c2), [nm] "v"(nm));
+    if (MODE == 6 || MODE == 7)  // MODE 0 with idle cycles behind it: s_sleep 1 (about 64 clocks) or s_sleep 3 (about 192)
+      asm volatile("v_mfma_f32_32x32x16_bf16 %[c0], %[a], %[b], %[c0]\n\t" T2A "v_mfma_f32_32x32x16_bf16 %[c1], %[a], %[b], %[c1]\n\t" T2B
+                   "v_mfma_f32_32x32x16_bf16 %[c2v], %[a], %[b], %[c2v]\n\t" T2A "v_mfma_f32_32x32x16_bf16 %[c3], %[a], %[b], %[c3]\n\t" T2B
+                   "s_sleep %[nap]\n\t"
+                   : [c0] "+v"(c0), [c1] "+v"(c1), [c2v] "+v"(c2v), [c3] "+v"(c3), [x0] "+v"(x0), [x1] "+v"(x1), [x2] "+v"(x2), [x3] "+v"(x3), [s0] "+v"(s0), [s1] "+v"(s1)
+                   : [a] "v"(a), [b] "v"(b), [c2] "v"(c2), [nm] "v"(nm), [nap] "n"(MODE == 6 ? 1 : 3));
     if (MODE == 1)  // the same with the accumulators in AccVGPRs
       asm volatile("v_mfma_f32_32x32x16_bf16 %[c0], %[a], %[b], %[c0]\n\t" T2A "v_mfma_f32_32x32x16_bf16 %[c1], %[a], %[b], %[c1]\n\t" T2B
                    "v_mfma_f32_32x32x16_bf16 %[c2v], %[a], %[b], %[c2v]\n\t" T2A "v_mfma_f32_32x32x16_bf16 %[c3], %[a], %[b], %[c3]\n\t" T2B
@@ -93,6 +100,8 @@ int main() {
     run<1>("4 x (MFMA 32x32x16 + 2 triples), AccVGPR accumulators", blocks, in, out, cyc);
     run<2>("8 x (MFMA 16x16x32 + 1 triple)", blocks, in, out, cyc);
     run<5>("4 MFMA 32x32x16, then 8 triples", blocks, in, out, cyc);
+    run<6>("4 x (MFMA 32x32x16 + 2 triples), then s_sleep 1", blocks, in, out, cyc);
+    run<7>("4 x (MFMA 32x32x16 + 2 triples), then s_sleep 3", blocks, in, out, cyc);
   }
   return 0;
 }
