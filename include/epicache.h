@@ -164,9 +164,13 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  * memory-bound copy proceeds beside the arithmetic-bound scoring instead of after it.  Results as
  * epicache_evict_step, except that the scores may differ from that call's in the last bits (the key splits of
  * the first scoring pass follow the size of the launch, and with them the order of a row's sum).
+ *   row_lse_opt      NULL, or the softmax normaliser of every scoring row as epicache_score_lse takes it
+ *                    ([n_batch, n_q_heads, patch_len] float32, dense): the scoring is then one pass over K
+ *                    (epicache_evict_step_lse over chunks); causal_patch must be 0.
  *   n_chunks         0 = chosen by the library (1, i.e. the plain step, where overlapping does not pay:
  *                    fewer than 256 scoring rows, no MFMA path, or nothing to evict); otherwise 1..64, and
- *                    never more than n_batch.  epicache_overlapped_workspace_size reports the number used.
+ *                    never more than n_batch.  epicache_overlapped_workspace_size reports the number used
+ *                    (with_row_lse: nonzero if row_lse_opt will be given; the library's choice depends on it).
  *   workspace        at least the size epicache_overlapped_workspace_size reports for the same params and
  *                    n_chunks (every chunk has its own slice; scores_opt / keep_idx_opt do not shrink it).
  *   hip_stream_aux   a second stream of the same device, default priority.  Equal to hip_stream: the chunks
@@ -179,10 +183,10 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  * on a device and keeps until the process ends (host-side objects; no device memory).  The device current at
  * the call must be the one both streams belong to.  Not for HIP graph capture. */
 EPICACHE_API int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks,
-                        size_t* bytes_out, int32_t* n_chunks_out);
+                        int32_t with_row_lse, size_t* bytes_out, int32_t* n_chunks_out);
 EPICACHE_API int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,
-                        float* scores_opt, int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
-                        size_t workspace_bytes, void* hip_stream, void* hip_stream_aux);
+                        const float* row_lse_opt, float* scores_opt, int32_t* keep_idx_opt, int32_t n_chunks,
+                        void* workspace, size_t workspace_bytes, void* hip_stream, void* hip_stream_aux);
 
 /* epicache_evict_step with the scoring done by epicache_score_lse: for callers whose prefill
  * attention kernel already returned each patch row's log-sum-exp (row_lse as documented there).

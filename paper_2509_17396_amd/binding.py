@@ -94,9 +94,9 @@ def load() -> ctypes.CDLL:
     lib.epicache_evict_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.epicache_evict_step_lse.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.epicache_overlapped_workspace_size.argtypes = [pp, ctypes.c_int32, ctypes.POINTER(sz),
+    lib.epicache_overlapped_workspace_size.argtypes = [pp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz),
                                                        ctypes.POINTER(ctypes.c_int32)]
-    lib.epicache_evict_step_overlapped.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp, vp]
+    lib.epicache_evict_step_overlapped.argtypes = [pp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, sz, vp, vp]
     lib.epicache_layer_budgets.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_double,
                                            ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     i32c = ctypes.c_int32
@@ -205,20 +205,22 @@ def epicache_evict_step_static(params: Params, q, k, v, scores=None, keep_idx=No
                                              _ptr(keep_idx), _stream()), "epicache_evict_step_static")
 
 
-def epicache_overlapped_workspace_size(params: Params, n_chunks: int = 0):
+def epicache_overlapped_workspace_size(params: Params, n_chunks: int = 0, with_row_lse: bool = False):
     """(bytes, number of chunks the step will use)"""
     out, used = ctypes.c_size_t(0), ctypes.c_int32(0)
-    _check(load().epicache_overlapped_workspace_size(ctypes.byref(params), n_chunks, ctypes.byref(out),
-                                                     ctypes.byref(used)), "epicache_overlapped_workspace_size")
+    _check(load().epicache_overlapped_workspace_size(ctypes.byref(params), n_chunks, int(with_row_lse),
+                                                     ctypes.byref(out), ctypes.byref(used)),
+           "epicache_overlapped_workspace_size")
     return out.value, used.value
 
 
 def epicache_evict_step_overlapped(params: Params, q, k, v, workspace, aux_stream, n_chunks: int = 0, scores=None,
-                                   keep_idx=None) -> None:
-    """aux_stream: a torch.cuda.Stream of the same device (the compactions run there)."""
-    _check(load().epicache_evict_step_overlapped(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(scores),
-                                                 _ptr(keep_idx), n_chunks, _ptr(workspace), workspace.numel(),
-                                                 _stream(), ctypes.c_void_p(aux_stream.cuda_stream)),
+                                   keep_idx=None, row_lse=None) -> None:
+    """aux_stream: a torch.cuda.Stream of the same device (selection and compaction run there)."""
+    _check(load().epicache_evict_step_overlapped(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(row_lse),
+                                                 _ptr(scores), _ptr(keep_idx), n_chunks, _ptr(workspace),
+                                                 workspace.numel(), _stream(),
+                                                 ctypes.c_void_p(aux_stream.cuda_stream)),
            "epicache_evict_step_overlapped")
 
 

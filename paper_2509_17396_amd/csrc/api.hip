@@ -335,7 +335,7 @@ struct OverlapPlan {
   size_t total;          // bytes: every chunk has its own workspace slice
 };
 
-static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, OverlapPlan* out) {
+static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, bool with_lse, OverlapPlan* out) {
   OverlapPlan op;
   int st = make_plan(prm, &op.whole);
   if (st != EPICACHE_OK) return st;
@@ -350,7 +350,7 @@ static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, Overl
     const int64_t nbh = (int64_t)pw.nb * pw.Hkv;
     n = 1;
     if (pw.use_mfma && pw.R >= 256 && pw.N > pw.M) {
-      const double flops = 4.0 * pw.R * (double)pw.N * pw.d * (double)nbh;
+      const double flops = (with_lse ? 2.0 : 4.0) * pw.R * (double)pw.N * pw.d * (double)nbh;  // one pass or two
       const double by_work = flops / 1.25e11;
       n = (int)(nbh / 64);
       if ((double)n > by_work) n = (int)by_work;
@@ -623,11 +623,11 @@ int epicache_evict_step_static(const epicache_params* params, const void* q, voi
                          kStaticScratchBytes, hip_stream);
 }
 
-int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks, size_t* bytes_out,
-                                       int32_t* n_chunks_out) {
+int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks, int32_t with_row_lse,
+                                       size_t* bytes_out, int32_t* n_chunks_out) {
   if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
   OverlapPlan op;
-  int st = make_overlap_plan(params, n_chunks, &op);
+  int st = make_overlap_plan(params, n_chunks, with_row_lse != 0, &op);
   if (st != EPICACHE_OK) return st;
   *bytes_out = op.total;
   if (n_chunks_out) *n_chunks_out = op.n_chunks;
@@ -635,14 +635,16 @@ int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_
 }
 
 int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,
-                                   float* scores_opt, int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream, void* hip_stream_aux) {
+                                   const float* row_lse_opt, float* scores_opt, int32_t* keep_idx_opt,
+                                   int32_t n_chunks, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                   void* hip_stream_aux) {
   OverlapPlan op;
-  int st = make_overlap_plan(params, n_chunks, &op);
+  int st = make_overlap_plan(params, n_chunks, row_lse_opt != nullptr, &op);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (row_lse_opt && op.whole.causal_patch) return EPICACHE_ERR_INVALID_ARG;  // as epicache_score_lse
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(workspace) || misaligned(scores_opt) ||
-      misaligned(keep_idx_opt))
+      misaligned(keep_idx_opt) || misaligned(row_lse_opt))
     return EPICACHE_ERR_INVALID_ARG;
   if (k == v) return EPICACHE_ERR_INVALID_ARG;
   if (workspace_bytes < op.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
@@ -670,13 +672,19 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
     float* scores = scores_opt ? scores_opt + b0 * pw.Hkv * pw.N : reinterpret_cast<float*>(wc + pc.off_scores);
     int32_t* keep = keep_idx_opt ? keep_idx_opt + b0 * pw.Hkv * pw.n_keep
                                  : reinterpret_cast<int32_t*>(wc + pc.off_keep);
+    // the caller's normalisers of this chunk's rows ([n_batch, n_q_heads, patch_len], dense)
+    const float* lse_c = row_lse_opt ? row_lse_opt + b0 * pw.Hq * pw.p : nullptr;
+    auto score = [&]() -> int {
+      return lse_c ? run_score_lse(pc, qc, kc, lse_c, scores, wc, main_stream)
+                   : run_score(pc, qc, kc, scores, wc, main_stream);
+    };
     if (pw.N <= pw.M) {  // nothing to evict: as epicache_evict_step
-      if (scores_opt) result = run_score(pc, qc, kc, scores, wc, main_stream);
+      if (scores_opt) result = score();
       if (result == EPICACHE_OK && keep_idx_opt && launch_iota_keep(pc, keep, main_stream) != hipSuccess)
         result = EPICACHE_ERR_DEVICE;
       continue;
     }
-    result = run_score(pc, qc, kc, scores, wc, main_stream);
+    result = score();
     if (result != EPICACHE_OK) break;
     hipStream_t rest_stream = main_stream;
     if (two_streams) {

@@ -108,6 +108,40 @@ def test_overlapped_step_matches_oracle(case, reduce):
         assert torch.equal(_bits(vv[:, :, :n_keep]), _bits(v_after[:, :, :n_keep]))
 
 
+@pytest.mark.parametrize("reduce", [orc.REDUCE_MAX, orc.REDUCE_SUM], ids=["max", "sum"])
+def test_overlapped_step_with_supplied_normalisers(reduce):
+    """row_lse_opt: the scoring of every chunk is the single pass of epicache_score_lse on that chunk's slice of the
+    caller's normalisers.  With normalisers taken over the context keys the result is Eq. 1 itself (the oracle's plain
+    score); the caches must be those of epicache_evict_step_lse bit for bit (the single pass has no key splits)."""
+    nb, Hq, Hkv, p, d, N, M = 7, 8, 2, 40, 128, 700, 256
+    say(f"overlapped with row_lse, 3 chunks, reduce={reduce}")
+    q, k0, v0 = _inputs(nb, Hq, Hkv, p, d, N, torch.bfloat16, seed=4242)
+    prm = ep.make_params(q, k0, n_cached=M, n_block=N - M, budget=M, reduce=reduce)
+    qq, kk = synth.to_f64_numpy(q), synth.to_f64_numpy(k0)
+    G = Hq // Hkv
+    z = np.einsum("bhgtd,bhnd->bhgtn", qq.reshape(nb, Hkv, G, p, d), kk) / np.sqrt(d)
+    zmax = z.max(axis=-1, keepdims=True)
+    lse_np = (zmax[..., 0] + np.log(np.exp(z - zmax).sum(axis=-1))).reshape(nb, Hq, p)   # natural log-sum-exp per row
+    lse = torch.from_numpy(lse_np.astype(np.float32)).to(DEV)
+    o_s = orc.score(qq, kk, N, reduce)
+    nbytes, used = ep.epicache_overlapped_workspace_size(prm, 3, with_row_lse=True)
+    assert used == 3
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    k, v = k0.clone(), v0.clone()
+    scores = torch.full((nb, Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
+    keep = torch.full((nb, Hkv, M), -1, dtype=torch.int32, device=DEV)
+    ep.epicache_evict_step_overlapped(prm, q, k, v, ws, torch.cuda.Stream(), 3, scores, keep, row_lse=lse)
+    k1, v1 = k0.clone(), v0.clone()
+    s1, i1 = torch.empty_like(scores), torch.empty_like(keep)
+    ep.epicache_evict_step_lse(prm, q, k1, v1, lse, ep.alloc_workspace(prm), s1, i1)
+    torch.cuda.synchronize()
+    rtol = pu.rtol_for(torch.bfloat16)
+    pu.assert_scores_close(scores.cpu().numpy(), o_s, rtol, "overlapped lse scores")
+    pu.assert_keep_matches(keep.cpu().numpy(), o_s, M, rtol, "overlapped lse keep")
+    assert torch.equal(scores.view(torch.int32), s1.view(torch.int32)) and torch.equal(keep, i1)
+    assert torch.equal(_bits(k[:, :, :M]), _bits(k1[:, :, :M])) and torch.equal(_bits(v[:, :, :M]), _bits(v1[:, :, :M]))
+
+
 def test_overlapped_calls_back_to_back_share_the_event_pool():
     """Three steps of a cache enqueued without a host synchronisation in between (each appends a block to what the
     previous one kept), the same sequence through the plain step: the events of one call are reused by the next
@@ -146,15 +180,21 @@ def test_overlapped_validation():
     prm = ep.make_params(q, k, n_cached=256, n_block=256, budget=256, reduce=ep.REDUCE_SUM)
     out, used = ctypes.c_size_t(0), ctypes.c_int32(0)
     for bad in (-1, 65):
-        assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), bad, ctypes.byref(out),
+        assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), bad, 0, ctypes.byref(out),
                                                       ctypes.byref(used)) == ep.ERR_INVALID_ARG
-    assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), 2, ctypes.byref(out), ctypes.byref(used)) == ep.OK
+    assert lib.epicache_overlapped_workspace_size(ctypes.byref(prm), 2, 0, ctypes.byref(out), ctypes.byref(used)) == ep.OK
     ws = torch.empty(out.value, dtype=torch.uint8, device=DEV)
     aux = torch.cuda.Stream()
-    st = lib.epicache_evict_step_overlapped(ctypes.byref(prm), q.data_ptr(), k.data_ptr(), v.data_ptr(), None, None, 2,
-                                            ws.data_ptr(), out.value - 256, None, ctypes.c_void_p(aux.cuda_stream))
+    st = lib.epicache_evict_step_overlapped(ctypes.byref(prm), q.data_ptr(), k.data_ptr(), v.data_ptr(), None, None, None,
+                                            2, ws.data_ptr(), out.value - 256, None, ctypes.c_void_p(aux.cuda_stream))
     assert st == ep.ERR_WORKSPACE_TOO_SMALL
-    st = lib.epicache_evict_step_overlapped(ctypes.byref(prm), q.data_ptr(), k.data_ptr(), k.data_ptr(), None, None, 2,
-                                            ws.data_ptr(), out.value, None, ctypes.c_void_p(aux.cuda_stream))
+    st = lib.epicache_evict_step_overlapped(ctypes.byref(prm), q.data_ptr(), k.data_ptr(), k.data_ptr(), None, None, None,
+                                            2, ws.data_ptr(), out.value, None, ctypes.c_void_p(aux.cuda_stream))
     assert st == ep.ERR_INVALID_ARG     # K and V must be distinct buffers
+    lse = torch.zeros(4, 8, 64, dtype=torch.float32, device=DEV)
+    prm.causal_patch = 1                # a supplied normaliser already fixes the denominator
+    st = lib.epicache_evict_step_overlapped(ctypes.byref(prm), q.data_ptr(), k.data_ptr(), v.data_ptr(), lse.data_ptr(),
+                                            None, None, 2, ws.data_ptr(), out.value, None,
+                                            ctypes.c_void_p(aux.cuda_stream))
+    assert st == ep.ERR_INVALID_ARG
     torch.cuda.synchronize()

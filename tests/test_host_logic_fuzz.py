@@ -125,7 +125,7 @@ def test_overlapped_plans_cover_the_batch_and_their_chunks(g, asked):
     lib = ep.load()
     size, plain, used = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int32(-1)
     st_plain = lib.epicache_workspace_size(ctypes.byref(prm), ctypes.byref(plain))
-    st_o = lib.epicache_overlapped_workspace_size(ctypes.byref(prm), asked, ctypes.byref(size), ctypes.byref(used))
+    st_o = lib.epicache_overlapped_workspace_size(ctypes.byref(prm), asked, 0, ctypes.byref(size), ctypes.byref(used))
     if st_plain != ep.OK:
         assert st_o == st_plain
         return
@@ -158,6 +158,7 @@ def test_overlapped_chunk_choice_for_the_benchmarked_workloads():
     tenth of a millisecond each, none where the scoring has fewer than 256 rows per head."""
     from paper_2509_17396_amd import synth
     want = {"tiny": 1, "llama32_3b": 1, "llama31_8b": 16, "qwen25_7b": 14, "stress": 64}
+    with_lse = {"tiny": 1, "llama32_3b": 1, "llama31_8b": 8, "qwen25_7b": 8, "stress": 64}
     for name, chunks in want.items():
         w = synth.WORKLOADS[name]
         nb, cap = w.L * w.E, w.M + w.B
@@ -165,6 +166,10 @@ def test_overlapped_chunk_choice_for_the_benchmarked_workloads():
         prm = ep.Params(ctypes.sizeof(ep.Params), nb, w.Hq, w.Hkv, w.d, w.M, w.B, w.M, w.p, dtype, ep.REDUCE_SUM, 0.0,
                         0, 0, w.Hq * w.p * w.d, w.p * w.d, w.d, w.Hkv * cap * w.d, cap * w.d, w.d)
         size, used = ctypes.c_size_t(0), ctypes.c_int32(0)
-        assert ep.load().epicache_overlapped_workspace_size(ctypes.byref(prm), 0, ctypes.byref(size),
+        assert ep.load().epicache_overlapped_workspace_size(ctypes.byref(prm), 0, 0, ctypes.byref(size),
                                                             ctypes.byref(used)) == ep.OK
         assert used.value == chunks, (name, used.value)
+        # with the caller's normalisers the scoring is one pass: half the work per chunk
+        assert ep.load().epicache_overlapped_workspace_size(ctypes.byref(prm), 0, 1, ctypes.byref(size),
+                                                            ctypes.byref(used)) == ep.OK
+        assert used.value == with_lse[name], (name, used.value)
