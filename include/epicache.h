@@ -181,7 +181,9 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  * or keep_idx_opt.
  * State: the events that order the two streams come from a pool the library creates on the first such call
  * on a device and keeps until the process ends (host-side objects; no device memory).  The device current at
- * the call must be the one both streams belong to.  Not for HIP graph capture. */
+ * the call must be the one both streams belong to.  The call may be captured into a HIP graph from `hip_stream`:
+ * `hip_stream_aux` joins the capture through the events and leaves it at the join (make the first call on a
+ * device outside a capture, so that the pool exists). */
 EPICACHE_API int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks,
                         int32_t with_row_lse, size_t* bytes_out, int32_t* n_chunks_out);
 EPICACHE_API int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,

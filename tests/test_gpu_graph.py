@@ -18,10 +18,13 @@ def say(msg):
     sys.stdout.flush()
 
 
-@pytest.mark.parametrize("ragged", [False, True], ids=["uniform", "ragged_pooled"])
-def test_evict_step_replays_from_a_graph(ragged):
-    w = synth.WORKLOADS["llama32_3b"].scaled(E=2, M=512, B=512)
-    say(f"graph capture, ragged={ragged}")
+@pytest.mark.parametrize("ragged,overlapped", [(False, False), (True, False), (False, True)],
+                         ids=["uniform", "ragged_pooled", "overlapped_two_streams"])
+def test_evict_step_replays_from_a_graph(ragged, overlapped):
+    """overlapped: epicache_evict_step_overlapped in two chunks; its second stream joins the capture through the
+    chunk events (fork) and the join event, and the event pool serves eager calls again afterwards."""
+    w = synth.WORKLOADS["llama32_3b"].scaled(E=4 if overlapped else 2, M=512, B=512)
+    say(f"graph capture, ragged={ragged}, overlapped={overlapped}")
     inputs = [synth.make_layer(w, layer=l, device=DEV) for l in range(3)]
     q, k, v = (t.clone() for t in inputs[0])
     nb, H, N = w.E, w.Hkv, w.N
@@ -32,6 +35,12 @@ def test_evict_step_replays_from_a_graph(ragged):
         n_ctx = torch.full((nb, H), N, dtype=torch.int32, device=DEV)
         n_ctx[0, 1], n_ctx[1, 3] = 700, 0
         n_kept = torch.zeros((nb, H), dtype=torch.int32, device=DEV)
+    elif overlapped:
+        cap = w.M
+        nbytes, used = ep.epicache_overlapped_workspace_size(prm, 2)
+        assert used == 2
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        aux = torch.cuda.Stream()
     else:
         cap = w.M
         ws = ep.alloc_workspace(prm)
@@ -41,6 +50,8 @@ def test_evict_step_replays_from_a_graph(ragged):
     def step():
         if ragged:
             ep.epicache_evict_step_ragged(prm, ep.SELECT_POOLED, q, k, v, n_ctx, None, n_kept, ws, scores, keep)
+        elif overlapped:
+            ep.epicache_evict_step_overlapped(prm, q, k, v, ws, aux, 2, scores, keep)
         else:
             ep.epicache_evict_step(prm, q, k, v, ws, scores, keep)
 
@@ -82,3 +93,8 @@ def test_evict_step_replays_from_a_graph(ragged):
             else:
                 assert torch.equal(g.view(torch.uint8) if g.dtype == torch.bfloat16 else g,
                                    e.view(torch.uint8) if e.dtype == torch.bfloat16 else e), f"replay on set {i}"
+    if overlapped:   # an eager call after the capture: the same events, recorded outside a capture again
+        load(2)
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(k.view(torch.uint8), want[2][2].view(torch.uint8))
