@@ -174,7 +174,9 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  *   workspace        at least the size epicache_overlapped_workspace_size reports for the same params and
  *                    n_chunks (every chunk has its own slice; scores_opt / keep_idx_opt do not shrink it).
  *   hip_stream_aux   a second stream of the same device, default priority.  Equal to hip_stream: the chunks
- *                    run one after the other on that stream.
+ *                    run one after the other on that stream.  HIP multiplexes streams onto a few hardware queues
+ *                    (GPU_MAX_HW_QUEUES, 4 by default): in a process with many streams make sure the two do not
+ *                    share one, or the step runs serially with the cost of its extra launches on top.
  * Ordering seen by the caller: everything is ordered after the work already enqueued on `hip_stream`, and
  * `hip_stream` waits for the last compaction before the call's successors run, so the call behaves like a
  * single-stream call; `hip_stream_aux` must carry no other work that touches K, V, the workspace, scores_opt
@@ -182,8 +184,8 @@ EPICACHE_API int epicache_evict_step_static(const epicache_params* params, const
  * State: the events that order the two streams come from a pool the library creates on the first such call
  * on a device and keeps until the process ends (host-side objects; no device memory).  The device current at
  * the call must be the one both streams belong to.  The call may be captured into a HIP graph from `hip_stream`:
- * `hip_stream_aux` joins the capture through the events and leaves it at the join (make the first call on a
- * device outside a capture, so that the pool exists). */
+ * `hip_stream_aux` joins the capture through events that live for the call only (the pool is not used then)
+ * and leaves it at the join. */
 EPICACHE_API int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_chunks,
                         int32_t with_row_lse, size_t* bytes_out, int32_t* n_chunks_out);
 EPICACHE_API int epicache_evict_step_overlapped(const epicache_params* params, const void* q, void* k, void* v,

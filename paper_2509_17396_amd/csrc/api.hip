@@ -652,12 +652,36 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
   hipStream_t main_stream = (hipStream_t)hip_stream, aux_stream = (hipStream_t)hip_stream_aux;
   const bool two_streams = main_stream != aux_stream && op.n_chunks > 1 && pw.N > pw.M;
 
+  // Under stream capture the events only shape the graph's edges and are not needed once the call returns: they
+  // are created for the call and destroyed at its end, so that the pool's events never belong to a capture.
   std::unique_lock<std::mutex> lock(overlap_mutex, std::defer_lock);
   OverlapEvents* ev = nullptr;
+  OverlapEvents capture_events;
+  bool capturing = false;
   if (two_streams) {
-    lock.lock();
-    ev = overlap_event_pool();
-    if (!ev) return EPICACHE_ERR_DEVICE;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(main_stream, &cs) != hipSuccess) {
+      (void)hipGetLastError();
+      cs = hipStreamCaptureStatusNone;
+    }
+    capturing = cs == hipStreamCaptureStatusActive;
+    if (capturing) {
+      int made = 0;
+      for (; made <= op.n_chunks; made++) {
+        hipEvent_t* slot = made < op.n_chunks ? &capture_events.chunk[made] : &capture_events.join;
+        if (hipEventCreateWithFlags(slot, hipEventDisableTiming) != hipSuccess) break;
+      }
+      if (made <= op.n_chunks) {
+        (void)hipGetLastError();
+        for (int i = 0; i < made; i++) (void)hipEventDestroy(capture_events.chunk[i]);
+        return EPICACHE_ERR_DEVICE;
+      }
+      ev = &capture_events;
+    } else {
+      lock.lock();
+      ev = overlap_event_pool();
+      if (!ev) return EPICACHE_ERR_DEVICE;
+    }
   }
   char* ws = static_cast<char*>(workspace);
   int result = EPICACHE_OK;
@@ -703,6 +727,10 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
     if (hipEventRecord(ev->join, aux_stream) != hipSuccess ||
         hipStreamWaitEvent(main_stream, ev->join, 0) != hipSuccess)
       result = EPICACHE_ERR_DEVICE;
+  }
+  if (capturing) {
+    for (int i = 0; i < op.n_chunks; i++) (void)hipEventDestroy(capture_events.chunk[i]);
+    (void)hipEventDestroy(capture_events.join);
   }
   return result;
 }
