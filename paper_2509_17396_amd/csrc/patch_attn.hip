@@ -82,10 +82,10 @@ __device__ __forceinline__ float max_across_halves(float x) {
 // hand-written v_max3_f32 scheduled straight behind the S chain read the accumulators before the matrix core
 // had written them (no wait states inserted).  The stale maximum is still a valid reference, so results stayed
 // inside the tolerance but differed from run to run in the last bf16 bit.
-// Two waves per SIMD (a cap of 256 registers per wave) when a workgroup has 3 or 4 waves; the 2-wave form keeps
-// the uncapped allocation.
+// Two waves per SIMD (a cap of 256 registers per wave): two workgroups per CU when a workgroup has 3 or 4 waves,
+// one when it has 8; the 2-wave form keeps the uncapped allocation.
 template <int NW>
-__global__ __launch_bounds__(NW * 64, NW >= 3 ? 2 : 1) void patch_attention_mfma(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(NW * 64, (NW >= 3 && NW < 8) ? 2 : 1) void patch_attention_mfma(const bf16_t* __restrict__ q,
                                                                    const bf16_t* __restrict__ k,
                                                                    const bf16_t* __restrict__ v,
                                                                    bf16_t* __restrict__ out,
@@ -350,10 +350,12 @@ void launch_mfma(const Plan& pl, const void* q, const void* k, const void* v, vo
 hipError_t launch_patch_attention(const Plan& pl, const void* q, const void* k, const void* v, void* out,
                                   float* lse, hipStream_t stream) {
   if (pl.dtype == EPICACHE_DTYPE_BF16 && pl.d == kHD) {
-    // waves per workgroup (32 rows each): four unless R itself is smaller, so that K and V tiles are
-    // re-read by as few row blocks as possible
-    const int best = pl.R <= 64 ? 2 : pl.R <= 96 ? 3 : 4;
-    if (best == 4) launch_mfma<4>(pl, q, k, v, out, lse, stream);
+    // waves per workgroup (32 rows each): as many as R fills, so that K and V tiles are staged by as few row
+    // blocks as possible.  Eight waves (one workgroup per CU) halve the L2 -> LDS traffic of four and are 2-3 %
+    // faster from 256 rows on, although the tile barrier then stops both waves of every SIMD at once.
+    const int best = pl.R <= 64 ? 2 : pl.R <= 96 ? 3 : pl.R < 256 ? 4 : 8;
+    if (best == 8) launch_mfma<8>(pl, q, k, v, out, lse, stream);
+    else if (best == 4) launch_mfma<4>(pl, q, k, v, out, lse, stream);
     else if (best == 3) launch_mfma<3>(pl, q, k, v, out, lse, stream);
     else launch_mfma<2>(pl, q, k, v, out, lse, stream);
     return hipGetLastError();

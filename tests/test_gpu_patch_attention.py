@@ -53,6 +53,8 @@ CASES = [
     ("bf16_mfma_R192_three_waves", "llama32_3b", dict(E=2, Hq=6, Hkv=2, p=64), 640),
     ("bf16_mfma_R128_four_waves", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=64), 500),
     ("bf16_mfma_R64_two_waves", "llama32_3b", dict(E=1, Hq=2, Hkv=2, p=64), 257),
+    ("bf16_mfma_R256_eight_waves", "llama31_8b", dict(E=2, Hq=8, Hkv=2, p=64), 520),
+    ("bf16_mfma_R448_eight_waves_one_idle", "qwen25_7b", dict(E=1, Hq=14, Hkv=2, p=64), 300),
     ("bf16_mfma_ragged_rows_p37", "llama32_3b", dict(E=1, Hq=6, Hkv=2, p=37), 1000),
     ("bf16_mfma_two_patch_tiles_p100", "llama31_8b", dict(E=1, Hq=8, Hkv=2, p=100), 777),
     ("bf16_mfma_one_context_key", "llama32_3b", dict(E=1, Hq=4, Hkv=2, p=16), 1),
