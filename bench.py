@@ -441,6 +441,9 @@ def main():
         roofline = {"kernel": "score (score_stats + score_reduce)", "bound": "mfma", "achieved": a,
                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": a / PEAK_BF16_MFMA_TFLOPS,
                     "traffic": score_traffic, "traffic_source": score_src,
+                    "launch": "whole batch per launch, timed with HIP events on the launch stream; the overlapped step "
+                              "launches the same kernels once per chunk beside the previous chunk's selection and "
+                              "compaction (per-chunk durations: profiles/kernels_<workload>_folded.txt, '@grid' rows)",
                     "executed": {"tflops": 2 * a, "frac_of_peak": 2 * a / PEAK_BF16_MFMA_TFLOPS,
                                  "sustained_tflops_for_this_instruction_mix": SUSTAINED_MFMA_SOFTMAX_TFLOPS,
                                  "frac_of_sustained": 2 * a / SUSTAINED_MFMA_SOFTMAX_TFLOPS,
