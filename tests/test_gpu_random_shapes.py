@@ -36,11 +36,8 @@ def draw_case(i):
                 spare=spare, seed=i)
 
 
-@pytest.mark.parametrize("i", range(N_CASES))
-def test_evict_step_random_shape(i):
-    c = draw_case(i)
-    print(f"[case] {c}", flush=True)
-    sys.stdout.flush()
+def run_case(c, i, overlapped_chunks=0):
+    """overlapped_chunks > 0: through epicache_evict_step_overlapped with that many chunks asked for."""
     w = synth.WORKLOADS["tiny"].scaled(E=c["E"], Hq=c["Hkv"] * c["G"], Hkv=c["Hkv"], d=c["d"], p=c["p"],
                                        dtype="bf16" if c["bf16"] else "f32", M=c["M"], B=1, recipe=c["recipe"],
                                        seed=0xE91C1000 + i)
@@ -51,11 +48,17 @@ def test_evict_step_random_shape(i):
     n_cached = min(M, N)
     prm = ep.make_params(qd, kd, n_cached=n_cached, n_block=N - n_cached, budget=M, reduce=c["reduce"],
                          causal_patch=c["causal"])
-    ws = ep.alloc_workspace(prm)
     n_keep = min(M, N)
     scores = torch.full((w.E, w.Hkv, N), float("nan"), dtype=torch.float32, device=DEV)
     keep = torch.full((w.E, w.Hkv, n_keep), -1, dtype=torch.int32, device=DEV)
-    ep.epicache_evict_step(prm, qd, kd, vd, ws, scores, keep)
+    if overlapped_chunks:
+        nbytes, used = ep.epicache_overlapped_workspace_size(prm, overlapped_chunks)
+        assert used == -(-w.E // -(-w.E // min(overlapped_chunks, w.E)))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+        ep.epicache_evict_step_overlapped(prm, qd, kd, vd, ws, torch.cuda.Stream(), overlapped_chunks, scores, keep)
+    else:
+        ws = ep.alloc_workspace(prm)
+        ep.epicache_evict_step(prm, qd, kd, vd, ws, scores, keep)
     torch.cuda.synchronize()
     scores, keep = scores.cpu().numpy(), keep.cpu().numpy()
     qq, kk = pu.oracle_inputs(q, k)
@@ -72,3 +75,24 @@ def test_evict_step_random_shape(i):
     else:
         np.testing.assert_array_equal(got_k, kb)
         np.testing.assert_array_equal(got_v, vb)
+
+
+@pytest.mark.parametrize("i", range(N_CASES))
+def test_evict_step_random_shape(i):
+    c = draw_case(i)
+    print(f"[case] {c}", flush=True)
+    sys.stdout.flush()
+    run_case(c, i)
+
+
+@pytest.mark.parametrize("i", range(48))
+def test_overlapped_step_random_shape(i):
+    """The same sweep through the two-stream pipeline: 2-9 batch items cut into 2-9 chunks (equal chunks, a shorter
+    last chunk, one item per chunk)."""
+    c = draw_case(1000 + i)
+    rng = np.random.default_rng(0x0E71 + i)
+    c["E"] = int(rng.integers(2, 10))
+    chunks = int(rng.integers(2, 10))
+    print(f"[case] overlapped, {chunks} chunks asked: {c}", flush=True)
+    sys.stdout.flush()
+    run_case(c, 1000 + i, overlapped_chunks=chunks)
