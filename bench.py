@@ -353,10 +353,24 @@ def measure(w, reduce_name, steps, warmup, stage_reps, extras, aux):
         torch.cuda.synchronize()
         t_ragged[tag] = mean_ms(ev[1:], 0)
         del wsr
+        # the same over chunks on two streams
+        rbytes, _, rchunks = ep.epicache_ragged_overlapped_workspace_size(prm, select, 0)
+        wsr = torch.empty(max(rbytes, 256), dtype=torch.uint8, device=dev)
+        ev = events(stage_reps + 1, 2)
+        for e in ev:
+            kp.copy_(kfresh), vp.copy_(vfresh)
+            e[0].record()
+            ep.epicache_evict_step_ragged_overlapped(prm, select, q0, kp, vp, n_ctx, budgets, n_kept, wsr, aux, 0)
+            e[1].record()
+        torch.cuda.synchronize()
+        t_ragged[tag + "_overlapped"] = mean_ms(ev[1:], 0)
+        del wsr
     stages["evict_step_ragged"] = {
         "ms_per_head": t_ragged["per_head"], "ms_pooled": t_ragged["pooled"],
-        "note": "epicache_evict_step_ragged on the same inputs, lengths and budgets read from device memory; "
-                "not part of the timed step"}
+        "overlapped_ms_per_head": t_ragged["per_head_overlapped"], "overlapped_ms_pooled": t_ragged["pooled_overlapped"],
+        "overlapped_chunks": rchunks,
+        "note": "epicache_evict_step_ragged / epicache_evict_step_ragged_overlapped on the same inputs, lengths and "
+                "budgets read from device memory; not part of the timed step"}
 
     # ---- the attention-free KeyDiff scorer on the same K (second workload of the same back end)
     ev = events(stage_reps + 1, 2)

@@ -258,6 +258,21 @@ EPICACHE_API int epicache_evict_step_ragged(const epicache_params* params, int32
                                             int32_t* keep_idx_opt, void* workspace, size_t workspace_bytes,
                                             void* hip_stream);
 
+/* epicache_evict_step_ragged as a two-stream pipeline over chunks of whole batch items, exactly as
+ * epicache_evict_step_overlapped does it for the uniform step (scoring of chunk c + 1 on `hip_stream` beside the
+ * selection and compaction of chunk c on `hip_stream_aux`; same ordering, state, capture and n_chunks rules, with
+ * N_max and params->budget in the place of N and M).  Every array is used in slices of whole batch items.  The
+ * workspace size, the keep capacity (as epicache_ragged_workspace_size reports it) and the number of chunks used come
+ * from epicache_ragged_overlapped_workspace_size. */
+EPICACHE_API int epicache_ragged_overlapped_workspace_size(const epicache_params* params, int32_t select,
+                                            int32_t n_chunks, int32_t with_row_lse, size_t* bytes_out,
+                                            int32_t* keep_capacity_out, int32_t* n_chunks_out);
+EPICACHE_API int epicache_evict_step_ragged_overlapped(const epicache_params* params, int32_t select, const void* q,
+                                            void* k, void* v, const int32_t* n_ctx, const int32_t* budgets,
+                                            const float* row_lse_opt, int32_t* n_kept, float* scores_opt,
+                                            int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream, void* hip_stream_aux);
+
 /* Sec. 2.3: the patched prompt's own pass through the attention layer.  For every patch query t of every
  * query head: out[b,hq,t,:] = sum_i softmax_i(scale * q.k_i) V[b,h,i,:] and lse_out[b,hq,t] = natural log of
  * sum_i exp(scale * q.k_i), over the N context rows and, with causal_patch = 1, the patch rows 0..t that

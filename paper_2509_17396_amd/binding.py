@@ -25,6 +25,7 @@ ENTRY_POINTS = (
     "epicache_workspace_size", "epicache_score", "epicache_score_lse", "epicache_topk", "epicache_compact",
     "epicache_evict_step", "epicache_evict_step_static", "epicache_evict_step_lse", "epicache_layer_budgets",
     "epicache_overlapped_workspace_size", "epicache_evict_step_overlapped",
+    "epicache_ragged_overlapped_workspace_size", "epicache_evict_step_ragged_overlapped",
     "epicache_ragged_workspace_size", "epicache_score_ragged", "epicache_select_ragged", "epicache_compact_ragged",
     "epicache_evict_step_ragged", "epicache_snapkv_workspace_size", "epicache_evict_step_snapkv",
     "epicache_kvzip_workspace_size", "epicache_score_kvzip", "epicache_evict_step_kvzip", "epicache_score_keydiff", "epicache_patch_attention",
@@ -105,6 +106,10 @@ def load() -> ctypes.CDLL:
     lib.epicache_select_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_compact_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_evict_step_ragged.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.epicache_ragged_overlapped_workspace_size.argtypes = [pp, i32c, i32c, i32c, ctypes.POINTER(sz),
+                                                              ctypes.POINTER(i32c), ctypes.POINTER(i32c)]
+    lib.epicache_evict_step_ragged_overlapped.argtypes = [pp, i32c, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32c, vp, sz,
+                                                          vp, vp]
     lib.epicache_snapkv_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
     lib.epicache_evict_step_snapkv.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.epicache_kvzip_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
@@ -269,6 +274,28 @@ def epicache_evict_step_ragged(params: Params, select: int, q, k, v, n_ctx, budg
                                              _ptr(n_ctx), _ptr(budgets), _ptr(row_lse), _ptr(n_kept), _ptr(scores),
                                              _ptr(keep_idx), _ptr(workspace), workspace.numel(), _stream()),
            "epicache_evict_step_ragged")
+
+
+def epicache_ragged_overlapped_workspace_size(params: Params, select: int, n_chunks: int = 0,
+                                              with_row_lse: bool = False):
+    """(bytes, keep capacity, number of chunks the step will use)"""
+    out, cap, used = ctypes.c_size_t(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().epicache_ragged_overlapped_workspace_size(ctypes.byref(params), int(select), n_chunks,
+                                                            int(with_row_lse), ctypes.byref(out), ctypes.byref(cap),
+                                                            ctypes.byref(used)),
+           "epicache_ragged_overlapped_workspace_size")
+    return out.value, cap.value, used.value
+
+
+def epicache_evict_step_ragged_overlapped(params: Params, select: int, q, k, v, n_ctx, budgets, n_kept, workspace,
+                                          aux_stream, n_chunks: int = 0, scores=None, keep_idx=None,
+                                          row_lse=None) -> None:
+    _check(load().epicache_evict_step_ragged_overlapped(ctypes.byref(params), int(select), _ptr(q), _ptr(k), _ptr(v),
+                                                        _ptr(n_ctx), _ptr(budgets), _ptr(row_lse), _ptr(n_kept),
+                                                        _ptr(scores), _ptr(keep_idx), n_chunks, _ptr(workspace),
+                                                        workspace.numel(), _stream(),
+                                                        ctypes.c_void_p(aux_stream.cuda_stream)),
+           "epicache_evict_step_ragged_overlapped")
 
 
 def epicache_patch_attention(params: Params, q, k, v, out, lse_out) -> None:

@@ -335,9 +335,15 @@ struct OverlapPlan {
   size_t total;          // bytes: every chunk has its own workspace slice
 };
 
-static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, bool with_lse, OverlapPlan* out) {
+// select < 0: the uniform step; otherwise the ragged step with that selection rule (plans with its keep pitch and
+// threshold records)
+static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, bool with_lse, int32_t select,
+                             OverlapPlan* out) {
   OverlapPlan op;
-  int st = make_plan(prm, &op.whole);
+  auto plan_of = [&](const epicache_params* p, Plan* pl) {
+    return select < 0 ? make_plan(p, pl) : make_ragged_plan(p, select, pl);
+  };
+  int st = plan_of(prm, &op.whole);
   if (st != EPICACHE_OK) return st;
   if (n_chunks < 0 || n_chunks > kMaxOverlapChunks) return EPICACHE_ERR_INVALID_ARG;
   const Plan& pw = op.whole;
@@ -364,12 +370,12 @@ static int make_overlap_plan(const epicache_params* prm, int32_t n_chunks, bool 
   op.tail_nb = pw.nb - (op.n_chunks - 1) * op.chunk_nb;
   epicache_params pc = *prm;
   pc.n_batch = op.chunk_nb;
-  st = make_plan(&pc, &op.body);
+  st = plan_of(&pc, &op.body);
   if (st != EPICACHE_OK) return st;
   op.tail = op.body;
   if (op.tail_nb != op.chunk_nb) {
     pc.n_batch = op.tail_nb;
-    st = make_plan(&pc, &op.tail);
+    st = plan_of(&pc, &op.tail);
     if (st != EPICACHE_OK) return st;
   }
   op.total = (size_t)(op.n_chunks - 1) * op.body.ws_total + op.tail.ws_total;
@@ -410,6 +416,77 @@ static OverlapEvents* overlap_event_pool() {
     ev.ready = true;
   }
   return &ev;
+}
+
+// The chunks of an overlapped step: score(c) on `main_stream`, rest(c) (selection and compaction) on `aux_stream`
+// behind an event that follows score(c); at the end `main_stream` waits for the last rest().  With a single chunk
+// or a single stream everything runs on `main_stream` in order.
+template <class ScoreFn, class RestFn>
+static int run_chunks_on_two_streams(int n_chunks, hipStream_t main_stream, hipStream_t aux_stream, ScoreFn score,
+                                     RestFn rest) {
+  const bool two_streams = main_stream != aux_stream && n_chunks > 1;
+  // Under stream capture the events only shape the graph's edges and are not needed once the call returns: they
+  // are created for the call and destroyed at its end, so that the pool's events never belong to a capture.
+  std::unique_lock<std::mutex> lock(overlap_mutex, std::defer_lock);
+  OverlapEvents* ev = nullptr;
+  OverlapEvents capture_events;
+  bool capturing = false;
+  if (two_streams) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(main_stream, &cs) != hipSuccess) {
+      (void)hipGetLastError();
+      cs = hipStreamCaptureStatusNone;
+    }
+    capturing = cs == hipStreamCaptureStatusActive;
+    if (capturing) {
+      int made = 0;
+      for (; made <= n_chunks; made++) {
+        hipEvent_t* slot = made < n_chunks ? &capture_events.chunk[made] : &capture_events.join;
+        if (hipEventCreateWithFlags(slot, hipEventDisableTiming) != hipSuccess) break;
+      }
+      if (made <= n_chunks) {
+        (void)hipGetLastError();
+        for (int i = 0; i < made; i++) (void)hipEventDestroy(capture_events.chunk[i]);
+        return EPICACHE_ERR_DEVICE;
+      }
+      ev = &capture_events;
+    } else {
+      lock.lock();
+      ev = overlap_event_pool();
+      if (!ev) return EPICACHE_ERR_DEVICE;
+    }
+  }
+  int result = EPICACHE_OK;
+  bool forked = false;
+  for (int c = 0; c < n_chunks && result == EPICACHE_OK; c++) {
+    result = score(c, main_stream);
+    if (result != EPICACHE_OK) break;
+    hipStream_t rest_stream = main_stream;
+    if (two_streams) {
+      // selection and compaction of this chunk wait for its scores only; the next chunk's scoring does not wait
+      // for them
+      if (hipEventRecord(ev->chunk[c], main_stream) != hipSuccess ||
+          hipStreamWaitEvent(aux_stream, ev->chunk[c], 0) != hipSuccess) {
+        result = EPICACHE_ERR_DEVICE;
+        break;
+      }
+      forked = true;
+      rest_stream = aux_stream;
+    }
+    result = rest(c, rest_stream);
+  }
+  if (forked) {
+    // join, also after a failed launch: whatever follows on the caller's stream is ordered after the work enqueued
+    // on the other stream so far
+    if (hipEventRecord(ev->join, aux_stream) != hipSuccess ||
+        hipStreamWaitEvent(main_stream, ev->join, 0) != hipSuccess)
+      result = EPICACHE_ERR_DEVICE;
+  }
+  if (capturing) {
+    for (int i = 0; i < n_chunks; i++) (void)hipEventDestroy(capture_events.chunk[i]);
+    (void)hipEventDestroy(capture_events.join);
+  }
+  return result;
 }
 
 }  // namespace epicache
@@ -627,7 +704,7 @@ int epicache_overlapped_workspace_size(const epicache_params* params, int32_t n_
                                        size_t* bytes_out, int32_t* n_chunks_out) {
   if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
   OverlapPlan op;
-  int st = make_overlap_plan(params, n_chunks, with_row_lse != 0, &op);
+  int st = make_overlap_plan(params, n_chunks, with_row_lse != 0, -1, &op);
   if (st != EPICACHE_OK) return st;
   *bytes_out = op.total;
   if (n_chunks_out) *n_chunks_out = op.n_chunks;
@@ -639,7 +716,7 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
                                    int32_t n_chunks, void* workspace, size_t workspace_bytes, void* hip_stream,
                                    void* hip_stream_aux) {
   OverlapPlan op;
-  int st = make_overlap_plan(params, n_chunks, row_lse_opt != nullptr, &op);
+  int st = make_overlap_plan(params, n_chunks, row_lse_opt != nullptr, -1, &op);
   if (st != EPICACHE_OK) return st;
   if (!q || !k || !v || !workspace) return EPICACHE_ERR_INVALID_ARG;
   if (row_lse_opt && op.whole.causal_patch) return EPICACHE_ERR_INVALID_ARG;  // as epicache_score_lse
@@ -650,89 +727,129 @@ int epicache_evict_step_overlapped(const epicache_params* params, const void* q,
   if (workspace_bytes < op.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
   const Plan& pw = op.whole;
   hipStream_t main_stream = (hipStream_t)hip_stream, aux_stream = (hipStream_t)hip_stream_aux;
-  const bool two_streams = main_stream != aux_stream && op.n_chunks > 1 && pw.N > pw.M;
-
-  // Under stream capture the events only shape the graph's edges and are not needed once the call returns: they
-  // are created for the call and destroyed at its end, so that the pool's events never belong to a capture.
-  std::unique_lock<std::mutex> lock(overlap_mutex, std::defer_lock);
-  OverlapEvents* ev = nullptr;
-  OverlapEvents capture_events;
-  bool capturing = false;
-  if (two_streams) {
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(main_stream, &cs) != hipSuccess) {
-      (void)hipGetLastError();
-      cs = hipStreamCaptureStatusNone;
-    }
-    capturing = cs == hipStreamCaptureStatusActive;
-    if (capturing) {
-      int made = 0;
-      for (; made <= op.n_chunks; made++) {
-        hipEvent_t* slot = made < op.n_chunks ? &capture_events.chunk[made] : &capture_events.join;
-        if (hipEventCreateWithFlags(slot, hipEventDisableTiming) != hipSuccess) break;
-      }
-      if (made <= op.n_chunks) {
-        (void)hipGetLastError();
-        for (int i = 0; i < made; i++) (void)hipEventDestroy(capture_events.chunk[i]);
-        return EPICACHE_ERR_DEVICE;
-      }
-      ev = &capture_events;
-    } else {
-      lock.lock();
-      ev = overlap_event_pool();
-      if (!ev) return EPICACHE_ERR_DEVICE;
-    }
-  }
   char* ws = static_cast<char*>(workspace);
-  int result = EPICACHE_OK;
-  bool forked = false;
-  for (int c = 0; c < op.n_chunks && result == EPICACHE_OK; c++) {
-    const Plan& pc = c + 1 < op.n_chunks ? op.body : op.tail;
+
+  struct Chunk {
+    const Plan* pl;
+    const char* q;
+    char *k, *v, *ws;
+    float* scores;
+    int32_t* keep;
+    const float* lse;
+  };
+  auto chunk = [&](int c) {
+    Chunk ch;
+    ch.pl = c + 1 < op.n_chunks ? &op.body : &op.tail;
     const int64_t b0 = (int64_t)c * op.chunk_nb;  // first batch item of the chunk
-    const char* qc = static_cast<const char*>(q) + b0 * pw.qsb * pw.elem;
-    char* kc = static_cast<char*>(k) + b0 * pw.ksb * pw.elem;
-    char* vc = static_cast<char*>(v) + b0 * pw.ksb * pw.elem;
-    char* wc = ws + (size_t)c * op.body.ws_total;
-    float* scores = scores_opt ? scores_opt + b0 * pw.Hkv * pw.N : reinterpret_cast<float*>(wc + pc.off_scores);
-    int32_t* keep = keep_idx_opt ? keep_idx_opt + b0 * pw.Hkv * pw.n_keep
-                                 : reinterpret_cast<int32_t*>(wc + pc.off_keep);
+    ch.q = static_cast<const char*>(q) + b0 * pw.qsb * pw.elem;
+    ch.k = static_cast<char*>(k) + b0 * pw.ksb * pw.elem;
+    ch.v = static_cast<char*>(v) + b0 * pw.ksb * pw.elem;
+    ch.ws = ws + (size_t)c * op.body.ws_total;
+    ch.scores = scores_opt ? scores_opt + b0 * pw.Hkv * pw.N : reinterpret_cast<float*>(ch.ws + ch.pl->off_scores);
+    ch.keep = keep_idx_opt ? keep_idx_opt + b0 * pw.Hkv * pw.n_keep
+                           : reinterpret_cast<int32_t*>(ch.ws + ch.pl->off_keep);
     // the caller's normalisers of this chunk's rows ([n_batch, n_q_heads, patch_len], dense)
-    const float* lse_c = row_lse_opt ? row_lse_opt + b0 * pw.Hq * pw.p : nullptr;
-    auto score = [&]() -> int {
-      return lse_c ? run_score_lse(pc, qc, kc, lse_c, scores, wc, main_stream)
-                   : run_score(pc, qc, kc, scores, wc, main_stream);
-    };
-    if (pw.N <= pw.M) {  // nothing to evict: as epicache_evict_step
-      if (scores_opt) result = score();
-      if (result == EPICACHE_OK && keep_idx_opt && launch_iota_keep(pc, keep, main_stream) != hipSuccess)
-        result = EPICACHE_ERR_DEVICE;
-      continue;
+    ch.lse = row_lse_opt ? row_lse_opt + b0 * pw.Hq * pw.p : nullptr;
+    return ch;
+  };
+  auto score = [&](int c, hipStream_t stream) -> int {
+    const Chunk ch = chunk(c);
+    return ch.lse ? run_score_lse(*ch.pl, ch.q, ch.k, ch.lse, ch.scores, ch.ws, stream)
+                  : run_score(*ch.pl, ch.q, ch.k, ch.scores, ch.ws, stream);
+  };
+  if (pw.N <= pw.M) {  // nothing to evict: as epicache_evict_step, chunk by chunk on the caller's stream
+    for (int c = 0; c < op.n_chunks; c++) {
+      if (scores_opt) {
+        st = score(c, main_stream);
+        if (st != EPICACHE_OK) return st;
+      }
+      const Chunk ch = chunk(c);
+      if (keep_idx_opt && launch_iota_keep(*ch.pl, ch.keep, main_stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
     }
-    result = score();
-    if (result != EPICACHE_OK) break;
-    hipStream_t rest_stream = main_stream;
-    if (two_streams) {
-      // selection and compaction of this chunk wait for its scores only; the next chunk's scoring does not wait
-      // for them
-      if (hipEventRecord(ev->chunk[c], main_stream) != hipSuccess ||
-          hipStreamWaitEvent(aux_stream, ev->chunk[c], 0) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
-      forked = true;
-      rest_stream = aux_stream;
-    }
-    if (launch_topk(pc, scores, keep, rest_stream) != hipSuccess) { result = EPICACHE_ERR_DEVICE; break; }
-    if (launch_compact(pc, keep, kc, vc, rest_stream) != hipSuccess) result = EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
   }
-  if (forked) {
-    // join, also after a failed launch: whatever follows on hip_stream is ordered after the work enqueued on the other stream so far
-    if (hipEventRecord(ev->join, aux_stream) != hipSuccess ||
-        hipStreamWaitEvent(main_stream, ev->join, 0) != hipSuccess)
-      result = EPICACHE_ERR_DEVICE;
-  }
-  if (capturing) {
-    for (int i = 0; i < op.n_chunks; i++) (void)hipEventDestroy(capture_events.chunk[i]);
-    (void)hipEventDestroy(capture_events.join);
-  }
-  return result;
+  auto select_and_compact = [&](int c, hipStream_t stream) -> int {
+    const Chunk ch = chunk(c);
+    if (launch_topk(*ch.pl, ch.scores, ch.keep, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    if (launch_compact(*ch.pl, ch.keep, ch.k, ch.v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  };
+  return run_chunks_on_two_streams(op.n_chunks, main_stream, aux_stream, score, select_and_compact);
+}
+
+int epicache_ragged_overlapped_workspace_size(const epicache_params* params, int32_t select, int32_t n_chunks,
+                                              int32_t with_row_lse, size_t* bytes_out, int32_t* keep_capacity_out,
+                                              int32_t* n_chunks_out) {
+  if (!bytes_out) return EPICACHE_ERR_INVALID_ARG;
+  OverlapPlan op;
+  int st = make_overlap_plan(params, n_chunks, with_row_lse != 0, select, &op);
+  if (st != EPICACHE_OK) return st;
+  *bytes_out = op.total;
+  if (keep_capacity_out) *keep_capacity_out = op.whole.keep_stride;
+  if (n_chunks_out) *n_chunks_out = op.n_chunks;
+  return EPICACHE_OK;
+}
+
+int epicache_evict_step_ragged_overlapped(const epicache_params* params, int32_t select, const void* q, void* k,
+                                          void* v, const int32_t* n_ctx, const int32_t* budgets,
+                                          const float* row_lse_opt, int32_t* n_kept, float* scores_opt,
+                                          int32_t* keep_idx_opt, int32_t n_chunks, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream, void* hip_stream_aux) {
+  OverlapPlan op;
+  int st = make_overlap_plan(params, n_chunks, row_lse_opt != nullptr, select, &op);
+  if (st != EPICACHE_OK) return st;
+  if (!q || !k || !v || !n_ctx || !n_kept || !workspace) return EPICACHE_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(n_ctx) || misaligned(budgets) ||
+      misaligned(row_lse_opt) || misaligned(n_kept) || misaligned(scores_opt) || misaligned(keep_idx_opt) ||
+      misaligned(workspace))
+    return EPICACHE_ERR_INVALID_ARG;
+  const Plan& pw = op.whole;
+  if (k == v || (row_lse_opt && pw.causal_patch)) return EPICACHE_ERR_INVALID_ARG;
+  if (workspace_bytes < op.total) return EPICACHE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t main_stream = (hipStream_t)hip_stream, aux_stream = (hipStream_t)hip_stream_aux;
+  char* ws = static_cast<char*>(workspace);
+
+  struct Chunk {
+    Plan pl;  // with this chunk's lengths
+    const char* q;
+    char *k, *v, *ws;
+    float* scores;
+    int32_t *keep, *n_kept;
+    const int32_t* budgets;
+    const float* lse;
+  };
+  auto chunk = [&](int c) {
+    Chunk ch;
+    ch.pl = c + 1 < op.n_chunks ? op.body : op.tail;
+    const int64_t b0 = (int64_t)c * op.chunk_nb;
+    ch.pl.n_ctx = n_ctx + b0 * pw.Hkv;
+    ch.q = static_cast<const char*>(q) + b0 * pw.qsb * pw.elem;
+    ch.k = static_cast<char*>(k) + b0 * pw.ksb * pw.elem;
+    ch.v = static_cast<char*>(v) + b0 * pw.ksb * pw.elem;
+    ch.ws = ws + (size_t)c * op.body.ws_total;
+    ch.scores = scores_opt ? scores_opt + b0 * pw.Hkv * pw.N : reinterpret_cast<float*>(ch.ws + ch.pl.off_scores);
+    ch.keep = keep_idx_opt ? keep_idx_opt + b0 * pw.Hkv * pw.keep_stride
+                           : reinterpret_cast<int32_t*>(ch.ws + ch.pl.off_keep);
+    ch.n_kept = n_kept + b0 * pw.Hkv;
+    ch.budgets = budgets ? budgets + b0 : nullptr;
+    ch.lse = row_lse_opt ? row_lse_opt + b0 * pw.Hq * pw.p : nullptr;
+    return ch;
+  };
+  auto score = [&](int c, hipStream_t stream) -> int {
+    const Chunk ch = chunk(c);
+    return ch.lse ? run_score_lse(ch.pl, ch.q, ch.k, ch.lse, ch.scores, ch.ws, stream)
+                  : run_score(ch.pl, ch.q, ch.k, ch.scores, ch.ws, stream);
+  };
+  auto select_and_compact = [&](int c, hipStream_t stream) -> int {
+    Chunk ch = chunk(c);
+    if (launch_select_ragged(ch.pl, select, ch.scores, ch.budgets, ch.keep, ch.n_kept, ch.ws + ch.pl.off_select,
+                             stream) != hipSuccess)
+      return EPICACHE_ERR_DEVICE;
+    ch.pl.n_kept = ch.n_kept;
+    if (launch_compact(ch.pl, ch.keep, ch.k, ch.v, stream) != hipSuccess) return EPICACHE_ERR_DEVICE;
+    return EPICACHE_OK;
+  };
+  return run_chunks_on_two_streams(op.n_chunks, main_stream, aux_stream, score, select_and_compact);
 }
 
 int epicache_evict_step_lse(const epicache_params* params, const void* q, void* k, void* v,

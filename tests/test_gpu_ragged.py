@@ -272,25 +272,36 @@ def test_compact_ragged_bit_exact(dtype, d):
 
 # ------------------------------------------------------------------- whole step
 
-def run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce, want_intermediates=True):
+def run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce, want_intermediates=True, chunks=0):
+    """chunks > 0: through epicache_evict_step_ragged_overlapped with that many chunks asked for."""
     qd, kd, vd = q.to(DEV), k.to(DEV).clone(), v.to(DEV).clone()
     prm = ep.make_params(qd, kd, n_cached=0, n_block=n_max, budget=m_max, reduce=reduce)
-    _, cap = ep.epicache_ragged_workspace_size(prm, select)
-    ws = ep.alloc_ragged_workspace(prm, select)
     nb, H = kd.shape[0], kd.shape[1]
+    if chunks:
+        nbytes, cap, used = ep.epicache_ragged_overlapped_workspace_size(prm, select, chunks)
+        assert cap == ep.epicache_ragged_workspace_size(prm, select)[1]
+        assert used == -(-nb // -(-nb // min(chunks, nb)))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+    else:
+        _, cap = ep.epicache_ragged_workspace_size(prm, select)
+        ws = ep.alloc_ragged_workspace(prm, select)
     n_kept = torch.full((nb, H), -1, dtype=torch.int32, device=DEV)
     scores = keep = None
     if want_intermediates:
         scores = torch.full((nb, H, n_max), float("nan"), dtype=torch.float32, device=DEV)
         keep = torch.full((nb, H, cap), -1, dtype=torch.int32, device=DEV)
-    ep.epicache_evict_step_ragged(prm, select, qd, kd, vd, i32(n_ctx), i32(budgets), n_kept, ws, scores, keep)
+    if chunks:
+        ep.epicache_evict_step_ragged_overlapped(prm, select, qd, kd, vd, i32(n_ctx), i32(budgets), n_kept, ws,
+                                                 torch.cuda.Stream(), chunks, scores, keep)
+    else:
+        ep.epicache_evict_step_ragged(prm, select, qd, kd, vd, i32(n_ctx), i32(budgets), n_kept, ws, scores, keep)
     torch.cuda.synchronize()
     return (None if scores is None else scores.cpu().numpy(), None if keep is None else keep.cpu().numpy(),
             n_kept.cpu().numpy(), kd.cpu(), vd.cpu())
 
 
-def check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, reduce, what):
-    scores, keep, n_kept, kd, vd = run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce)
+def check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, reduce, what, chunks=0):
+    scores, keep, n_kept, kd, vd = run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce, chunks=chunks)
     rtol = pu.rtol_for(q.dtype)
     rows = orc.score_ragged(*pu.oracle_inputs(q, k), n_ctx, reduce)
     nb, H = n_kept.shape
@@ -310,7 +321,7 @@ def check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, red
             np.testing.assert_array_equal(gv[b, h, :n], vb[b, h][got_keep[b][h]])
             np.testing.assert_array_equal(gk[b, h, n:], kb[b, h, n:])
     # the workspace-only variant gives the same cache and counts
-    _, _, n_kept2, kd2, vd2 = run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce, False)
+    _, _, n_kept2, kd2, vd2 = run_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, reduce, False, chunks)
     assert (n_kept2 == n_kept).all()
     assert torch.equal(kd2.view(torch.uint8), kd.view(torch.uint8)) and torch.equal(vd2.view(torch.uint8), vd.view(torch.uint8))
     return differ, n_kept
@@ -436,3 +447,30 @@ def test_evict_step_ragged_random_shape(i):
     n_ctx.reshape(-1)[int(rng.integers(0, n_ctx.size))] = n_max
     budgets = [int(x) for x in rng.integers(1, m_max + 1, size=E)]
     check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, reduce, f"random {i}")
+
+
+@pytest.mark.parametrize("i", range(30))
+def test_evict_step_ragged_overlapped_random_shape(i):
+    """The same sweep through epicache_evict_step_ragged_overlapped: 2-7 batch items in 2-7 chunks, every array
+    used in slices of whole items (lengths, budgets, counts, scores, kept indices)."""
+    rng = np.random.default_rng(0x0AD4 + i)
+    bf16 = bool(rng.integers(0, 2))
+    d = int(rng.choice([64, 128])) if (bf16 and rng.random() < 0.7) else int(8 * rng.integers(1, 33))
+    Hkv, G = int(rng.integers(1, 5)), int(rng.choice([1, 2, 3, 4]))
+    p = int(rng.choice([1, 7, 32, 33, 64, 90]))
+    n_max = int(rng.choice([2, 64, 65, 129, 256, 300, 513, 700]))
+    E = int(rng.integers(2, 8))
+    chunks = int(rng.integers(2, 8))
+    m_max = int(rng.choice([1, max(1, n_max // 3), max(1, n_max // 2), n_max + 3]))
+    select, pooled = SELECTS[int(rng.integers(0, 2))]
+    reduce = int(rng.integers(0, 2))
+    w = wl("tiny", E=E, Hq=Hkv * G, Hkv=Hkv, d=d, p=p, dtype="bf16" if bf16 else "f32", M=m_max, B=1,
+           recipe=str(rng.choice(["normal", "outlier_channels", "student_t"])), seed=0xE91C3000 + i)
+    say(f"evict_step_ragged_overlapped random {i}: bf16={bf16} d={d} Hkv={Hkv} G={G} p={p} n_max={n_max} E={E} "
+        f"chunks={chunks} m_max={m_max} pooled={pooled} reduce={reduce}")
+    q, k, v = synth.make_layer(w, layer=i, n_ctx=n_max)
+    n_ctx = rng.integers(0, n_max + 1, size=(E, Hkv))
+    n_ctx.reshape(-1)[int(rng.integers(0, n_ctx.size))] = n_max
+    budgets = [int(x) for x in rng.integers(1, m_max + 1, size=E)]
+    check_ragged_step(q, k, v, n_ctx, budgets, m_max, n_max, select, pooled, reduce, f"overlapped random {i}",
+                      chunks=chunks)
