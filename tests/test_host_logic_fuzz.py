@@ -173,3 +173,29 @@ def test_overlapped_chunk_choice_for_the_benchmarked_workloads():
         assert ep.load().epicache_overlapped_workspace_size(ctypes.byref(prm), 0, 1, ctypes.byref(size),
                                                             ctypes.byref(used)) == ep.OK
         assert used.value == with_lse[name], (name, used.value)
+
+
+@settings(max_examples=200, deadline=None)
+@given(geometry, st.integers(1, 64), st.sampled_from([ep.SELECT_PER_HEAD, ep.SELECT_POOLED]))
+def test_ragged_overlapped_plans_are_sums_of_ragged_chunk_plans(g, asked, select):
+    nb, Hkv, G, p, d, n_cached, n_block, budget, dtype, reduce, causal, extra, pad = g
+    prm = _dense_params(*g)
+    lib = ep.load()
+    plain, cap = ctypes.c_size_t(0), ctypes.c_int32(0)
+    st_plain = lib.epicache_ragged_workspace_size(ctypes.byref(prm), select, ctypes.byref(plain), ctypes.byref(cap))
+    size, cap_o, used = ctypes.c_size_t(0), ctypes.c_int32(-1), ctypes.c_int32(-1)
+    st_o = lib.epicache_ragged_overlapped_workspace_size(ctypes.byref(prm), select, asked, 0, ctypes.byref(size),
+                                                         ctypes.byref(cap_o), ctypes.byref(used))
+    assert st_o == st_plain
+    if st_plain != ep.OK:
+        return
+    assert cap_o.value == cap.value
+    per = -(-nb // min(asked, nb))
+    n = -(-nb // per)
+    assert used.value == n
+    body, tail, c2 = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_int32(0)
+    assert lib.epicache_ragged_workspace_size(ctypes.byref(_dense_params(per, *g[1:])), select, ctypes.byref(body),
+                                              ctypes.byref(c2)) == ep.OK
+    assert lib.epicache_ragged_workspace_size(ctypes.byref(_dense_params(nb - (n - 1) * per, *g[1:])), select,
+                                              ctypes.byref(tail), ctypes.byref(c2)) == ep.OK
+    assert size.value == (n - 1) * body.value + tail.value
